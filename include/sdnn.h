@@ -1,0 +1,160 @@
+/*
+ * sdnn: sparse-DNN feed-forward / back-propagation / SGD update on one AMD
+ * MI355X (gfx950).  C ABI; plain pointers and sizes only.
+ *
+ * The library computes the sequential SGD method for sparse layered networks
+ * (Section 3.2, Eqs. 3-7, Algorithm 1) in its minibatch form (Section 5.1:
+ * the B sample vectors are the columns of a matrix X and every per-layer
+ * product becomes W X):
+ *
+ *   forward   X_l = f(W_l X_{l-1} + b_l 1^T),  l = 1..L          (Eq. 3)
+ *             f(z) = min(max(z, 0), act_cap)
+ *   backward  Delta_L = dLoss (.) f'(Z_L)                        (Eq. 6)
+ *             Delta_{l-1} = (W_l^T Delta_l) (.) f'(Z_{l-1})      (Eq. 7)
+ *   update    W_l(j,i) -= lr * sum_s Delta_l(j,s) X_{l-1}(i,s)   (Eqs. 4-5)
+ *             for the stored entries (j,i) of W_l only; the sparsity pattern
+ *             never changes.  b_l(j) -= lr * sum_s Delta_l(j,s) (the bias is
+ *             the weight of a link from a constant-one neuron, Section 3.2).
+ *
+ * f'(z) is 1 for 0 < z < act_cap and 0 elsewhere; it is evaluated from the
+ * stored output x = f(z).  Back-propagation uses the weights of the forward
+ * pass (Algorithm 1 forms delta^{k-1} before it updates W^k); every update is
+ * applied by sdnn_sgd_step.  Delta_0 is not formed.
+ *
+ * Arithmetic: fp32 storage, every sum accumulated in fp64 and rounded once
+ * when stored.  No atomics: results are bit-reproducible from run to run.
+ *
+ * Layouts
+ *   W_l        n_out x n_in, CSR: row_ptr int32[n_out+1], col_idx int32[nnz]
+ *              (strictly ascending inside a row), values fp32[nnz];
+ *              W_l(j,i) links neuron i of layer l-1 to neuron j of layer l.
+ *   X, Delta   dense fp32 [neurons][B], row-major: the B samples of one neuron
+ *              are contiguous (leading dimension B).
+ *
+ * Pointers named d_* are DEVICE pointers, all others are HOST pointers.
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ * device work is enqueued on that stream and is asynchronous; argument and
+ * state errors are reported synchronously.  The library never allocates device
+ * memory: the caller hands in one workspace at sdnn_create and keeps it alive
+ * until sdnn_destroy.
+ *
+ * Every function that returns int returns SDNN_OK or a negative code and never
+ * throws or aborts; sdnn_last_error gives the message of the last failure.
+ */
+#ifndef SDNN_H
+#define SDNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SDNN_OK 0
+#define SDNN_EINVAL (-1) /* null pointer, malformed CSR, size out of range   */
+#define SDNN_ESTATE (-2) /* call order violated, or net is not in training mode */
+#define SDNN_ENOMEM (-3) /* workspace too small / host allocation failed     */
+#define SDNN_EHIP (-4)   /* the HIP runtime reported an error                 */
+
+typedef struct sdnn_net sdnn_net; /* opaque */
+
+/* One layer, HOST arrays, copied by sdnn_create (the caller may free them). */
+typedef struct {
+    int32_t n_out, n_in;
+    const int32_t *row_ptr; /* [n_out+1], row_ptr[0] == 0, non-decreasing      */
+    const int32_t *col_idx; /* [nnz], in [0, n_in), strictly ascending per row */
+    const float *values;    /* [nnz]                                           */
+    const float *bias;      /* [n_out] or NULL (= zeros)                       */
+} sdnn_layer;
+
+typedef struct {
+    float act_cap;       /* activation cap; +INFINITY = plain ReLU; must be > 0  */
+    int32_t max_batch;   /* largest B a forward call may use (sizes the workspace) */
+    int32_t training;    /* 1: keep X_0..X_L and Delta_1..Delta_L; 0: inference only */
+    int32_t update_bias; /* 1: sdnn_sgd_step also updates the biases             */
+} sdnn_config;
+
+/* ---- setup (Algorithm 1's inputs {W^k}; the paper likewise precomputes its
+ *      per-layer index maps once, outside the timed iterations) ------------- */
+
+/* Number of workspace bytes sdnn_create needs for these layers and config. */
+int sdnn_workspace_bytes(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg,
+                         size_t *bytes);
+
+/* Validates the layers (consecutive layers must agree: n_in(l+1) == n_out(l)),
+ * builds the transposed index of every W_l and the row schedules, and copies
+ * everything into d_workspace (device, 256-byte aligned, >= workspace bytes).
+ * Synchronises `stream` before returning.  On failure *out is NULL. */
+int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg,
+                void *d_workspace, size_t workspace_bytes, void *stream, sdnn_net **out);
+
+/* Frees the host-side handle only (the workspace belongs to the caller). */
+void sdnn_destroy(sdnn_net *net);
+
+/* ---- the three passes --------------------------------------------------- */
+
+/* Eq. 3 for l = 1..L on a block of B samples (1 <= B <= max_batch).
+ * d_X0 [n_in(1)][B] in; d_XL [n_out(L)][B] out (may be NULL in training mode).
+ * In training mode X_0..X_L are kept in the workspace (X_0 is copied). */
+int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream);
+
+/* Eqs. 6-7.  d_dLoss [n_out(L)][B] = dJ/dX_L of the caller's loss, B as in the
+ * forward call that must directly precede it.  Training mode only. */
+int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream);
+
+/* Eqs. 4-5 on every layer, confined to the stored pattern.  Needs a preceding
+ * sdnn_backward and consumes it (a second step is SDNN_ESTATE). */
+int sdnn_sgd_step(sdnn_net *net, float lr, void *stream);
+
+/* ---- inspection (parity tests, checkpoints) ------------------------------
+ * All copy into caller-provided DEVICE buffers on `stream`. */
+int sdnn_get_activation(sdnn_net *net, int32_t layer /*0..L*/, float *d_dst, void *stream);
+int sdnn_get_delta(sdnn_net *net, int32_t layer /*1..L*/, float *d_dst, void *stream);
+/* Eq. 4 without applying it: d_g [nnz(layer)] in CSR order, d_gb [n_out] (either may be NULL).
+ * layer in 1..L; needs a preceding sdnn_backward (does not consume it). */
+int sdnn_weight_grad(sdnn_net *net, int32_t layer, float *d_g, float *d_gb, void *stream);
+int sdnn_get_weights(sdnn_net *net, int32_t layer /*1..L*/, float *d_values, float *d_bias,
+                     void *stream);
+int sdnn_set_weights(sdnn_net *net, int32_t layer /*1..L*/, const float *d_values,
+                     const float *d_bias, void *stream);
+/* Sizes of layer 1..L: any output pointer may be NULL. */
+int sdnn_layer_shape(const sdnn_net *net, int32_t layer, int32_t *n_out, int32_t *n_in,
+                     int64_t *nnz);
+
+/* ---- loss gradients of the two benchmark losses (the library itself is
+ *      loss-agnostic: only dJ/dX_L enters, Eq. 6) --------------------------- */
+
+/* J = 1/(2B) sum ||x_s - y_s||^2  =>  d_out = (X_L - Y)/B, all [n][B]. */
+int sdnn_mse_dloss(const float *d_XL, const float *d_Y, int32_t n, int32_t B, float *d_out,
+                   void *stream);
+/* J = -1/B sum_s log softmax(last n_classes rows of X_L)[label_s]
+ *  =>  d_out = (softmax - onehot)/B on those rows, 0 elsewhere.  d_labels int32[B]. */
+int sdnn_softmax_ce_dloss(const float *d_XL, const int32_t *d_labels, int32_t n, int32_t B,
+                          int32_t n_classes, float *d_out, void *stream);
+
+/* ---- host-only pieces of the setup, exported so they can be checked
+ *      without a GPU (all pointers HOST) ------------------------------------ */
+
+/* SDNN_OK or SDNN_EINVAL (message via sdnn_last_error(NULL)). */
+int sdnn_check_csr(int32_t n_out, int32_t n_in, const int32_t *row_ptr, const int32_t *col_idx);
+/* Transposed index of a pattern: for column i of W, t_row_ptr[i]..t_row_ptr[i+1]
+ * lists the rows j (ascending) holding an entry (j,i) in t_row_idx, and in
+ * t_perm the position of that entry in the CSR arrays (so W^T needs no second
+ * copy of the values).  t_row_ptr [n_in+1], t_row_idx/t_perm [nnz]. */
+int sdnn_transpose_pattern(int32_t n_out, int32_t n_in, const int32_t *row_ptr,
+                           const int32_t *col_idx, int32_t *t_row_ptr, int32_t *t_row_idx,
+                           int32_t *t_perm);
+/* Row schedule: the rows ordered by decreasing number of stored entries (the
+ * paper's per-row cost, Section 5), ties by ascending row.  order [n_rows]. */
+int sdnn_row_schedule(int32_t n_rows, const int32_t *row_ptr, int32_t *order);
+
+/* Message of the last failure on this net, or (net == NULL) of the last
+ * failure of a call that had no net, on the calling thread. */
+const char *sdnn_last_error(const sdnn_net *net);
+const char *sdnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDNN_H */

@@ -65,6 +65,11 @@ class Oracle:
     def _arr(self, a):
         return np.ascontiguousarray(a, dtype=self.dtype)
 
+    def _cap(self, cap: float) -> float:
+        """The cap is a number of the storage precision, like the activations
+        clamped to it: only then does 'x < cap' on a stored output mean 'z < cap'."""
+        return float(self.dtype.type(cap))
+
     # ---- per-layer operations -------------------------------------------
     def forward_layer(self, layer, x_in: np.ndarray, cap: float) -> np.ndarray:
         x_in = self._arr(x_in)
@@ -75,7 +80,7 @@ class Oracle:
         bias = None if layer.bias is None else self._arr(layer.bias)
         self._fn("oracle_forward_layer")(
             ctypes.c_int32(layer.n_out), _ptr(layer.row_ptr), _ptr(layer.col_idx), _ptr(vals),
-            _ptr(bias), _ptr(x_in), ctypes.c_int32(b), ctypes.c_double(cap), _ptr(out))
+            _ptr(bias), _ptr(x_in), ctypes.c_int32(b), ctypes.c_double(self._cap(cap)), _ptr(out))
         return out
 
     def output_delta(self, dloss: np.ndarray, x_last: np.ndarray, cap: float) -> np.ndarray:
@@ -85,7 +90,7 @@ class Oracle:
         out = np.empty_like(x_last)
         self._fn("oracle_output_delta")(
             ctypes.c_int32(x_last.shape[0]), ctypes.c_int32(x_last.shape[1]), _ptr(dloss),
-            _ptr(x_last), ctypes.c_double(cap), _ptr(out))
+            _ptr(x_last), ctypes.c_double(self._cap(cap)), _ptr(out))
         return out
 
     def backward_layer(self, layer, delta: np.ndarray, x_prev: Optional[np.ndarray],
@@ -101,7 +106,7 @@ class Oracle:
         self._fn("oracle_backward_layer")(
             ctypes.c_int32(layer.n_out), ctypes.c_int32(layer.n_in), _ptr(layer.row_ptr),
             _ptr(layer.col_idx), _ptr(vals), _ptr(delta), _ptr(x_prev), ctypes.c_int32(b),
-            ctypes.c_double(cap), _ptr(out))
+            ctypes.c_double(self._cap(cap)), _ptr(out))
         return out
 
     def weight_grad(self, layer, delta: np.ndarray, x_prev: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

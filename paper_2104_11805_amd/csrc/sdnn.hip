@@ -1,0 +1,771 @@
+// libsdnn: HIP kernels (gfx950) and the C-ABI entry points that launch them.
+//
+// Mapping to the hardware (64-wide wavefronts, no matrix cores: none of the
+// three passes is a dense contraction):
+//   * forward / backward product: one wavefront per matrix row, the 64 lanes
+//     walk the row together and each lane owns V consecutive samples, so the
+//     row's column indices and weights are wave-uniform (scalar loads) and each
+//     gathered activation row is one contiguous 256*V-byte read.  Each lane adds
+//     its terms in storage order in fp64: the sum is the same as a sequential
+//     CPU loop's, whatever the batch size.
+//   * pattern-confined gradient: one wavefront per row, lanes split as
+//     4 edge groups x 16 sample lanes, so that only a 16-lane butterfly is
+//     needed per 8 edges before the weight is rewritten in place.
+//   * W^T is never stored: the transposed index lists, per column, the source
+//     rows and the positions of the values in the CSR array.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sdnn_internal.h"
+
+// ---------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------
+
+#define WAVES_PER_BLOCK 4
+#define BLOCK_THREADS (64 * WAVES_PER_BLOCK)
+
+template <int V> __device__ __forceinline__ void ldv(const float *p, float (&x)[V]);
+template <> __device__ __forceinline__ void ldv<1>(const float *p, float (&x)[1]) { x[0] = *p; }
+template <> __device__ __forceinline__ void ldv<2>(const float *p, float (&x)[2])
+{
+    const float2 t = *reinterpret_cast<const float2 *>(p);
+    x[0] = t.x; x[1] = t.y;
+}
+template <> __device__ __forceinline__ void ldv<4>(const float *p, float (&x)[4])
+{
+    const float4 t = *reinterpret_cast<const float4 *>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+template <int V> __device__ __forceinline__ void stv(float *p, const float (&x)[V]);
+template <> __device__ __forceinline__ void stv<1>(float *p, const float (&x)[1]) { *p = x[0]; }
+template <> __device__ __forceinline__ void stv<2>(float *p, const float (&x)[2])
+{
+    *reinterpret_cast<float2 *>(p) = make_float2(x[0], x[1]);
+}
+template <> __device__ __forceinline__ void stv<4>(float *p, const float (&x)[4])
+{
+    *reinterpret_cast<float4 *>(p) = make_float4(x[0], x[1], x[2], x[3]);
+}
+
+// Workgroup ids are handed to the 8 XCDs round-robin and each XCD has its own
+// L2.  Give every XCD whole batch tiles (all row groups of tile x, x+8, ...)
+// so that the activation slab of a tile is gathered through one L2 only.  The
+// tiles left over when the tile count is not a multiple of 8 are shared.
+__device__ __forceinline__ void map_block(unsigned bid, unsigned n_tiles, unsigned n_rg,
+                                          unsigned &tile, unsigned &rg)
+{
+    const unsigned t8 = n_tiles & ~7u;
+    const unsigned n8 = t8 * n_rg;
+    if (bid < n8) {
+        const unsigned xcd = bid & 7u, k = bid >> 3;
+        tile = xcd + 8u * (k / n_rg);
+        rg = k % n_rg;
+    } else {
+        const unsigned k = bid - n8;
+        tile = t8 + k / n_rg;
+        rg = k % n_rg;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// K1 / K2: row-per-wavefront sparse product with fused epilogue
+//   MODE 0 (forward, Eq. 3):   out = min(max(sum + bias[row], 0), cap)
+//   MODE 1 (backward, Eq. 7):  out = sum * [0 < Xprev[row] < cap]; the values
+//                              are read through the transposed index (perm)
+// ---------------------------------------------------------------------------
+struct SpmmArgs {
+    const int32_t *row_ptr;
+    const int32_t *idx;
+    const float *vals;
+    const int32_t *perm;  // MODE 1 only
+    const int32_t *order; // rows by decreasing length
+    const float *in;      // [n_cols][B]
+    float *out;           // [n_rows][B]
+    const float *aux;     // MODE 0: bias [n_rows] (may be NULL); MODE 1: Xprev [n_rows][B]
+    int32_t n_rows, B;
+    uint32_t n_tiles, n_rg;
+    float cap;
+};
+
+template <int V, int MODE>
+__global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    unsigned tile, rg;
+    map_block(blockIdx.x, a.n_tiles, a.n_rg, tile, rg);
+    const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
+    if (r >= a.n_rows) return;
+    const int s = (int)tile * (64 * V) + lane * V;
+    if (s >= a.B) return;
+    const int row = a.order[r];
+    const int beg = a.row_ptr[row], end = a.row_ptr[row + 1];
+    const size_t ld = (size_t)a.B;
+    const float *in = a.in + s;
+
+    double acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+
+    constexpr int U = 8;
+    int p = beg;
+    for (; p + U <= end; p += U) {
+        float w[U];
+        float x[U][V];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int c = a.idx[p + k];
+            w[k] = MODE == 1 ? a.vals[a.perm[p + k]] : a.vals[p + k];
+            ldv<V>(in + (size_t)c * ld, x[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const double wk = (double)w[k];
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+        }
+    }
+    for (; p < end; ++p) {
+        const int c = a.idx[p];
+        const double wk = (double)(MODE == 1 ? a.vals[a.perm[p]] : a.vals[p]);
+        float x[V];
+        ldv<V>(in + (size_t)c * ld, x);
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[v], acc[v]);
+    }
+
+    float o[V];
+    const double cap = (double)a.cap;
+    if (MODE == 0) {
+        const double b = a.aux ? (double)a.aux[row] : 0.0;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            double z = acc[v] + b;
+            z = z < 0.0 ? 0.0 : z;
+            z = z > cap ? cap : z;
+            o[v] = (float)z;
+        }
+    } else {
+        float xp[V];
+        ldv<V>(a.aux + (size_t)row * ld + s, xp);
+#pragma unroll
+        for (int v = 0; v < V; ++v) o[v] = (xp[v] > 0.0f && xp[v] < a.cap) ? (float)acc[v] : 0.0f;
+    }
+    stv<V>(a.out + (size_t)row * ld + s, o);
+}
+
+// ---------------------------------------------------------------------------
+// K3: output delta (Eq. 6):  D = dLoss * [0 < X_L < cap]
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_output_delta(const float *__restrict__ dloss,
+                                                      const float *__restrict__ xl,
+                                                      float *__restrict__ d, size_t n, float cap)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const float x = xl[e];
+        d[e] = (x > 0.0f && x < cap) ? dloss[e] : 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// K4: gradient on the stored pattern (Eq. 4) fused with the update (Eq. 5)
+//   blockIdx.y = layer, one wavefront per row.  Lane = 16*eg + sg: edge group
+//   eg handles 8 consecutive entries of a 32-entry chunk of the row, sample
+//   lane sg handles samples sg*V + 16*V*t.  A 16-lane butterfly then leaves
+//   the 8 sums of an edge group in 8 different lanes, which write them back.
+//   emit == 0: vals -= lr*g, bias -= lr*gb (if update_bias)
+//   emit == 1: g_out / gb_out receive the gradient of the single layer
+// ---------------------------------------------------------------------------
+template <int V>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+k_update(const LayerDev *__restrict__ layers, int layer0, int B, float lr, int update_bias,
+         int emit, float *__restrict__ g_out, float *__restrict__ gb_out)
+{
+    const LayerDev &L = layers[layer0 + blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int r = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
+    if (r >= L.n_out) return;
+    const int row = L.order[r];
+    const int beg = L.row_ptr[row], end = L.row_ptr[row + 1];
+    const size_t ld = (size_t)B;
+    const float *drow = L.D + (size_t)row * ld;
+    const float *xp = L.X_prev;
+    const double dlr = (double)lr;
+
+    // bias gradient: sum of the row of Delta over the samples
+    if (emit ? gb_out != nullptr : update_bias != 0) {
+        double sum = 0.0;
+        for (int s = lane * V; s < B; s += 64 * V) {
+            float d[V];
+            ldv<V>(drow + s, d);
+#pragma unroll
+            for (int v = 0; v < V; ++v) sum += (double)d[v];
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+        if (lane == 0) {
+            const float gb = (float)sum;
+            if (emit) gb_out[row] = gb;
+            else L.bias[row] = (float)((double)L.bias[row] - dlr * (double)gb);
+        }
+    }
+    if (emit && g_out == nullptr) return;
+
+    const int sg = lane & 15, eg = lane >> 4;
+    for (int base = beg; base < end; base += 32) {
+        const int p0 = base + eg * 8;
+        size_t coff[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int p = p0 + k;
+            coff[k] = (size_t)(p < end ? L.col_idx[p] : L.col_idx[beg]) * ld;
+        }
+        double a[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) a[k] = 0.0;
+        for (int s = sg * V; s < B; s += 16 * V) {
+            float df[V];
+            ldv<V>(drow + s, df);
+            float x[8][V];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) ldv<V>(xp + coff[k] + s, x[k]);
+            double d[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) d[v] = (double)df[v];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
+        }
+        // 16-lane transpose-reduce: 8 values/lane -> 1 value/lane
+#pragma unroll
+        for (int half = 4, bit = 8; half >= 1; half >>= 1, bit >>= 1) {
+            const bool up = (lane & bit) != 0;
+#pragma unroll
+            for (int j = 0; j < half; ++j) {
+                const double send = up ? a[j] : a[j + half];
+                const double keep = up ? a[j + half] : a[j];
+                a[j] = keep + __shfl_xor(send, bit);
+            }
+        }
+        a[0] += __shfl_xor(a[0], 1);
+        const int k = ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 + ((lane >> 1) & 1);
+        const int p = p0 + k;
+        if ((lane & 1) == 0 && p < end) {
+            const float g = (float)a[0];
+            if (emit) g_out[p] = g;
+            else L.vals[p] = (float)((double)L.vals[p] - dlr * (double)g);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// loss-gradient helpers
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_mse_dloss(const float *__restrict__ x,
+                                                   const float *__restrict__ y,
+                                                   float *__restrict__ out, size_t n, double B)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x)
+        out[e] = (float)(((double)x[e] - (double)y[e]) / B);
+}
+
+__global__ void __launch_bounds__(256) k_softmax_ce_dloss(const float *__restrict__ x,
+                                                          const int32_t *__restrict__ labels,
+                                                          float *__restrict__ out, int n, int B,
+                                                          int n_classes)
+{
+    const int first = n - n_classes;
+    // zero the rows that carry no logit
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < (size_t)first * B;
+         e += (size_t)gridDim.x * blockDim.x)
+        out[e] = 0.0f;
+    for (int s = blockIdx.x * blockDim.x + threadIdx.x; s < B; s += gridDim.x * blockDim.x) {
+        double m = -INFINITY;
+        for (int c = 0; c < n_classes; ++c) m = fmax(m, (double)x[(size_t)(first + c) * B + s]);
+        double z = 0.0;
+        for (int c = 0; c < n_classes; ++c) z += exp((double)x[(size_t)(first + c) * B + s] - m);
+        const int lab = labels[s];
+        for (int c = 0; c < n_classes; ++c) {
+            double pr = exp((double)x[(size_t)(first + c) * B + s] - m) / z;
+            if (c == lab) pr -= 1.0;
+            out[(size_t)(first + c) * B + s] = (float)(pr / (double)B);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+enum { ST_IDLE = 0, ST_FORWARD = 1, ST_BACKWARD = 2 };
+
+struct sdnn_net {
+    int32_t n_layers = 0;
+    sdnn_config cfg{};
+    std::vector<LayerDev> layers; // host copy of the descriptors (device pointers inside)
+    LayerDev *d_layers = nullptr; // device copy
+    float *d_x0 = nullptr;        // training: X_0 [n_in(1)][max_batch]
+    float *d_ping = nullptr, *d_pong = nullptr; // inference: two activation buffers
+    int state = ST_IDLE;
+    int32_t B = 0;
+    int32_t max_n = 0;
+    char err[512] = "";
+};
+
+static int fail(sdnn_net *net, int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (net) snprintf(net->err, sizeof net->err, "%s", buf);
+    sdnn_set_global_error("%s", buf);
+    return code;
+}
+
+#define HIP_TRY(net, expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(net, SDNN_EHIP, "%s: %s", #expr, hipGetErrorString(e_));              \
+    } while (0)
+
+extern "C" const char *sdnn_last_error(const sdnn_net *net)
+{
+    return net ? net->err : sdnn_global_error();
+}
+
+static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Workspace plan: offsets of every array, in one pass (also used to size it).
+struct Plan {
+    struct PerLayer {
+        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, order, t_order, X, D;
+    };
+    std::vector<PerLayer> pl;
+    size_t table = 0, x0 = 0, ping = 0, pong = 0, total = 0;
+};
+
+static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg)
+{
+    if (!layers || !cfg) return fail(nullptr, SDNN_EINVAL, "layers or cfg is NULL");
+    if (n_layers < 1) return fail(nullptr, SDNN_EINVAL, "n_layers must be >= 1");
+    if (cfg->max_batch < 1) return fail(nullptr, SDNN_EINVAL, "max_batch must be >= 1");
+    if (!(cfg->act_cap > 0.0f)) return fail(nullptr, SDNN_EINVAL, "act_cap must be > 0 (or +inf)");
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const sdnn_layer &y = layers[l];
+        if (y.n_out < 0 || y.n_in < 0 || !y.row_ptr)
+            return fail(nullptr, SDNN_EINVAL, "layer %d: bad size or NULL row_ptr", l + 1);
+        if (l > 0 && y.n_in != layers[l - 1].n_out)
+            return fail(nullptr, SDNN_EINVAL, "layer %d: n_in %d != n_out %d of layer %d", l + 1,
+                        y.n_in, layers[l - 1].n_out, l);
+        if ((int64_t)y.n_out * cfg->max_batch >= ((int64_t)1 << 40))
+            return fail(nullptr, SDNN_EINVAL, "layer %d: activation block too large", l + 1);
+    }
+    return SDNN_OK;
+}
+
+static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg, Plan &pl)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    pl.pl.resize(n_layers);
+    pl.table = take(sizeof(LayerDev) * (size_t)n_layers);
+    const size_t mb = (size_t)cfg->max_batch;
+    size_t max_n = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const sdnn_layer &y = layers[l];
+        const size_t nnz = (size_t)y.row_ptr[y.n_out];
+        Plan::PerLayer &q = pl.pl[l];
+        q.row_ptr = take(4 * ((size_t)y.n_out + 1));
+        q.col_idx = take(4 * nnz);
+        q.vals = take(4 * nnz);
+        q.bias = take(4 * (size_t)y.n_out);
+        q.t_row_ptr = take(4 * ((size_t)y.n_in + 1));
+        q.t_row_idx = take(4 * nnz);
+        q.t_perm = take(4 * nnz);
+        q.order = take(4 * (size_t)y.n_out);
+        q.t_order = take(4 * (size_t)y.n_in);
+        q.X = q.D = 0;
+        if (cfg->training) {
+            q.X = take(4 * (size_t)y.n_out * mb);
+            q.D = take(4 * (size_t)y.n_out * mb);
+        }
+        max_n = std::max(max_n, (size_t)std::max(y.n_out, y.n_in));
+    }
+    if (cfg->training) {
+        pl.x0 = take(4 * (size_t)layers[0].n_in * mb);
+    } else {
+        pl.ping = take(4 * max_n * mb);
+        pl.pong = take(4 * max_n * mb);
+    }
+    pl.total = off;
+}
+
+extern "C" int sdnn_workspace_bytes(const sdnn_layer *layers, int32_t n_layers,
+                                    const sdnn_config *cfg, size_t *bytes)
+{
+    if (!bytes) return fail(nullptr, SDNN_EINVAL, "bytes is NULL");
+    int rc = check_config(layers, n_layers, cfg);
+    if (rc) return rc;
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (layers[l].row_ptr[0] != 0 || layers[l].row_ptr[layers[l].n_out] < 0)
+            return fail(nullptr, SDNN_EINVAL, "layer %d: malformed row_ptr", l + 1);
+    Plan pl;
+    make_plan(layers, n_layers, cfg, pl);
+    *bytes = pl.total;
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg,
+                           void *d_workspace, size_t workspace_bytes, void *stream_,
+                           sdnn_net **out)
+{
+    if (!out) return fail(nullptr, SDNN_EINVAL, "out is NULL");
+    *out = nullptr;
+    int rc = check_config(layers, n_layers, cfg);
+    if (rc) return rc;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        rc = sdnn_check_csr(layers[l].n_out, layers[l].n_in, layers[l].row_ptr, layers[l].col_idx);
+        if (rc) return fail(nullptr, rc, "layer %d: %s", l + 1, sdnn_global_error());
+        if (layers[l].row_ptr[layers[l].n_out] > 0 && !layers[l].values)
+            return fail(nullptr, SDNN_EINVAL, "layer %d: values is NULL", l + 1);
+    }
+    if (!d_workspace) return fail(nullptr, SDNN_EINVAL, "d_workspace is NULL");
+    if (((uintptr_t)d_workspace & 255) != 0)
+        return fail(nullptr, SDNN_EINVAL, "d_workspace must be 256-byte aligned");
+    Plan pl;
+    make_plan(layers, n_layers, cfg, pl);
+    if (workspace_bytes < pl.total)
+        return fail(nullptr, SDNN_ENOMEM, "workspace too small: %zu < %zu", workspace_bytes, pl.total);
+
+    hipStream_t stream = (hipStream_t)stream_;
+    sdnn_net *net = new (std::nothrow) sdnn_net;
+    if (!net) return fail(nullptr, SDNN_ENOMEM, "host allocation failed");
+    net->n_layers = n_layers;
+    net->cfg = *cfg;
+    net->layers.resize(n_layers);
+    char *base = (char *)d_workspace;
+    auto fail_free = [&](int code) { delete net; return code; };
+
+    std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
+    std::vector<float> zeros;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const sdnn_layer &y = layers[l];
+        const Plan::PerLayer &q = pl.pl[l];
+        const size_t nnz = (size_t)y.row_ptr[y.n_out];
+        t_row_ptr.resize((size_t)y.n_in + 1);
+        t_row_idx.resize(nnz);
+        t_perm.resize(nnz);
+        order.resize(y.n_out);
+        t_order.resize(y.n_in);
+        sdnn_transpose_pattern(y.n_out, y.n_in, y.row_ptr, y.col_idx, t_row_ptr.data(),
+                               t_row_idx.data(), t_perm.data());
+        sdnn_row_schedule(y.n_out, y.row_ptr, order.data());
+        sdnn_row_schedule(y.n_in, t_row_ptr.data(), t_order.data());
+
+        LayerDev &d = net->layers[l];
+        d.n_out = y.n_out; d.n_in = y.n_in; d.nnz = (int32_t)nnz; d.pad_ = 0;
+        d.row_ptr = (const int32_t *)(base + q.row_ptr);
+        d.col_idx = (const int32_t *)(base + q.col_idx);
+        d.vals = (float *)(base + q.vals);
+        d.bias = (float *)(base + q.bias);
+        d.t_row_ptr = (const int32_t *)(base + q.t_row_ptr);
+        d.t_row_idx = (const int32_t *)(base + q.t_row_idx);
+        d.t_perm = (const int32_t *)(base + q.t_perm);
+        d.order = (const int32_t *)(base + q.order);
+        d.t_order = (const int32_t *)(base + q.t_order);
+        d.X = cfg->training ? (float *)(base + q.X) : nullptr;
+        d.D = cfg->training ? (float *)(base + q.D) : nullptr;
+        d.X_prev = !cfg->training ? nullptr
+                   : l == 0       ? (float *)(base + pl.x0)
+                                  : net->layers[l - 1].X;
+        net->max_n = std::max(net->max_n, std::max(y.n_out, y.n_in));
+
+        const float *bias = y.bias;
+        if (!bias) { zeros.assign((size_t)y.n_out, 0.0f); bias = zeros.data(); }
+#define UP(dst, src, bytes)                                                                   \
+    do {                                                                                      \
+        if ((bytes) > 0) {                                                                    \
+            hipError_t e_ = hipMemcpyAsync((void *)(dst), (src), (bytes), hipMemcpyHostToDevice, stream); \
+            if (e_ == hipSuccess) e_ = hipStreamSynchronize(stream);                          \
+            if (e_ != hipSuccess)                                                             \
+                return fail_free(fail(nullptr, SDNN_EHIP, "upload: %s", hipGetErrorString(e_))); \
+        }                                                                                     \
+    } while (0)
+        UP(d.row_ptr, y.row_ptr, 4 * ((size_t)y.n_out + 1));
+        UP(d.col_idx, y.col_idx, 4 * nnz);
+        UP(d.vals, y.values, 4 * nnz);
+        UP(d.bias, bias, 4 * (size_t)y.n_out);
+        UP(d.t_row_ptr, t_row_ptr.data(), 4 * ((size_t)y.n_in + 1));
+        UP(d.t_row_idx, t_row_idx.data(), 4 * nnz);
+        UP(d.t_perm, t_perm.data(), 4 * nnz);
+        UP(d.order, order.data(), 4 * (size_t)y.n_out);
+        UP(d.t_order, t_order.data(), 4 * (size_t)y.n_in);
+    }
+    net->d_layers = (LayerDev *)(base + pl.table);
+    UP(net->d_layers, net->layers.data(), sizeof(LayerDev) * (size_t)n_layers);
+#undef UP
+    if (cfg->training) {
+        net->d_x0 = (float *)(base + pl.x0);
+    } else {
+        net->d_ping = (float *)(base + pl.ping);
+        net->d_pong = (float *)(base + pl.pong);
+    }
+    *out = net;
+    return SDNN_OK;
+}
+
+extern "C" void sdnn_destroy(sdnn_net *net) { delete net; }
+
+static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Samples per lane for the row-per-wavefront product: as wide as the batch
+// and the alignment of the operands allow without idling most of the wave.
+static int pick_v_spmm(int B, const void *a, const void *b, const void *c)
+{
+    if (B % 4 == 0 && B > 128 && aligned(a, 16) && aligned(b, 16) && aligned(c, 16)) return 4;
+    if (B % 2 == 0 && B > 64 && aligned(a, 8) && aligned(b, 8) && aligned(c, 8)) return 2;
+    return 1;
+}
+
+template <int MODE>
+static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float *out,
+                       const float *aux, int B, hipStream_t stream)
+{
+    SpmmArgs a;
+    if (MODE == 0) {
+        a.row_ptr = d.row_ptr; a.idx = d.col_idx; a.perm = nullptr; a.order = d.order;
+        a.n_rows = d.n_out;
+    } else {
+        a.row_ptr = d.t_row_ptr; a.idx = d.t_row_idx; a.perm = d.t_perm; a.order = d.t_order;
+        a.n_rows = d.n_in;
+    }
+    a.vals = d.vals; a.in = in; a.out = out; a.aux = aux; a.B = B; a.cap = net->cfg.act_cap;
+    if (a.n_rows == 0) return SDNN_OK;
+    const int V = pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
+    a.n_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
+    a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    const uint64_t blocks = (uint64_t)a.n_tiles * a.n_rg;
+    if (blocks > 0x7fffffffull) return fail(net, SDNN_EINVAL, "grid too large");
+    dim3 grid((unsigned)blocks), block(BLOCK_THREADS);
+    if (V == 4) hipLaunchKernelGGL((k_spmm<4, MODE>), grid, block, 0, stream, a);
+    else if (V == 2) hipLaunchKernelGGL((k_spmm<2, MODE>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((k_spmm<1, MODE>), grid, block, 0, stream, a);
+    HIP_TRY(net, hipGetLastError());
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!d_X0) return fail(net, SDNN_EINVAL, "d_X0 is NULL");
+    if (B < 1 || B > net->cfg.max_batch)
+        return fail(net, SDNN_EINVAL, "B = %d outside 1..max_batch = %d", B, net->cfg.max_batch);
+    const bool training = net->cfg.training != 0;
+    if (!training && !d_XL) return fail(net, SDNN_EINVAL, "d_XL is NULL");
+    hipStream_t stream = (hipStream_t)stream_;
+    net->state = ST_IDLE;
+    const int L = net->n_layers;
+    const float *in = d_X0;
+    if (training) {
+        const size_t bytes = 4 * (size_t)net->layers[0].n_in * B;
+        if (bytes) HIP_TRY(net, hipMemcpyAsync(net->d_x0, d_X0, bytes, hipMemcpyDeviceToDevice, stream));
+        in = net->d_x0;
+    }
+    for (int l = 0; l < L; ++l) {
+        const LayerDev &d = net->layers[l];
+        float *out = training ? d.X : (l == L - 1 ? d_XL : ((l & 1) ? net->d_pong : net->d_ping));
+        int rc = launch_spmm<0>(net, d, in, out, d.bias, B, stream);
+        if (rc) return rc;
+        in = out;
+    }
+    if (training && d_XL) {
+        const size_t bytes = 4 * (size_t)net->layers[L - 1].n_out * B;
+        if (bytes) HIP_TRY(net, hipMemcpyAsync(d_XL, net->layers[L - 1].X, bytes, hipMemcpyDeviceToDevice, stream));
+    }
+    net->B = B;
+    net->state = ST_FORWARD;
+    return SDNN_OK;
+}
+
+static unsigned ew_blocks(size_t n)
+{
+    size_t b = (n + 255) / 256;
+    return (unsigned)std::min<size_t>(std::max<size_t>(b, 1), 8192);
+}
+
+extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!net->cfg.training) return fail(net, SDNN_ESTATE, "net was not created for training");
+    if (net->state != ST_FORWARD)
+        return fail(net, SDNN_ESTATE, "sdnn_backward needs a directly preceding sdnn_forward");
+    if (!d_dLoss) return fail(net, SDNN_EINVAL, "d_dLoss is NULL");
+    hipStream_t stream = (hipStream_t)stream_;
+    const int L = net->n_layers, B = net->B;
+    const LayerDev &last = net->layers[L - 1];
+    const size_t n = (size_t)last.n_out * B;
+    if (n) {
+        hipLaunchKernelGGL(k_output_delta, dim3(ew_blocks(n)), dim3(256), 0, stream, d_dLoss, last.X,
+                           last.D, n, net->cfg.act_cap);
+        HIP_TRY(net, hipGetLastError());
+    }
+    for (int l = L - 1; l >= 1; --l) {
+        const LayerDev &d = net->layers[l];
+        // Delta_{l} (0-based l-1) = (W^T Delta_{l+1}) masked by X_{l}
+        int rc = launch_spmm<1>(net, d, d.D, net->layers[l - 1].D, d.X_prev, B, stream);
+        if (rc) return rc;
+    }
+    net->state = ST_BACKWARD;
+    return SDNN_OK;
+}
+
+static int pick_v_update(int B, const void *a, const void *b)
+{
+    return (B % 4 == 0 && aligned(a, 16) && aligned(b, 16)) ? 4 : 1;
+}
+
+static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int emit, float *g,
+                         float *gb, hipStream_t stream)
+{
+    int max_rows = 0;
+    for (int l = layer0; l < layer0 + n_layers; ++l) max_rows = std::max(max_rows, net->layers[l].n_out);
+    if (max_rows == 0) return SDNN_OK;
+    const int B = net->B;
+    // all activation / delta buffers are 256-byte aligned; rows are aligned iff B % 4 == 0
+    const int V = pick_v_update(B, net->layers[layer0].D, net->layers[layer0].X_prev);
+    for (int l0 = 0; l0 < n_layers; l0 += 65535) {
+        const int nl = std::min(65535, n_layers - l0);
+        dim3 grid((unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), (unsigned)nl);
+        if (V == 4)
+            hipLaunchKernelGGL(k_update<4>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
+                               layer0 + l0, B, lr, net->cfg.update_bias, emit, g, gb);
+        else
+            hipLaunchKernelGGL(k_update<1>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
+                               layer0 + l0, B, lr, net->cfg.update_bias, emit, g, gb);
+        HIP_TRY(net, hipGetLastError());
+    }
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_sgd_step(sdnn_net *net, float lr, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!net->cfg.training) return fail(net, SDNN_ESTATE, "net was not created for training");
+    if (net->state != ST_BACKWARD)
+        return fail(net, SDNN_ESTATE, "sdnn_sgd_step needs a preceding sdnn_backward");
+    int rc = launch_update(net, 0, net->n_layers, lr, 0, nullptr, nullptr, (hipStream_t)stream_);
+    if (rc) return rc;
+    net->state = ST_IDLE;
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_weight_grad(sdnn_net *net, int32_t layer, float *d_g, float *d_gb, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!net->cfg.training) return fail(net, SDNN_ESTATE, "net was not created for training");
+    if (net->state != ST_BACKWARD)
+        return fail(net, SDNN_ESTATE, "sdnn_weight_grad needs a preceding sdnn_backward");
+    if (layer < 1 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
+    if (!d_g && !d_gb) return SDNN_OK;
+    return launch_update(net, layer - 1, 1, 0.0f, 1, d_g, d_gb, (hipStream_t)stream_);
+}
+
+static int copy_dd(sdnn_net *net, void *dst, const void *src, size_t bytes, void *stream_)
+{
+    if (bytes) HIP_TRY(net, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream_));
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_get_activation(sdnn_net *net, int32_t layer, float *d_dst, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!net->cfg.training) return fail(net, SDNN_ESTATE, "activations are kept in training mode only");
+    if (net->state == ST_IDLE && net->B == 0) return fail(net, SDNN_ESTATE, "no forward pass yet");
+    if (layer < 0 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
+    if (!d_dst) return fail(net, SDNN_EINVAL, "d_dst is NULL");
+    const float *src = layer == 0 ? net->d_x0 : net->layers[layer - 1].X;
+    const size_t n = layer == 0 ? net->layers[0].n_in : net->layers[layer - 1].n_out;
+    return copy_dd(net, d_dst, src, 4 * n * net->B, stream_);
+}
+
+extern "C" int sdnn_get_delta(sdnn_net *net, int32_t layer, float *d_dst, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!net->cfg.training) return fail(net, SDNN_ESTATE, "deltas are kept in training mode only");
+    if (net->state != ST_BACKWARD) return fail(net, SDNN_ESTATE, "no backward pass to read");
+    if (layer < 1 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
+    if (!d_dst) return fail(net, SDNN_EINVAL, "d_dst is NULL");
+    return copy_dd(net, d_dst, net->layers[layer - 1].D, 4 * (size_t)net->layers[layer - 1].n_out * net->B, stream_);
+}
+
+extern "C" int sdnn_get_weights(sdnn_net *net, int32_t layer, float *d_values, float *d_bias, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (layer < 1 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
+    const LayerDev &d = net->layers[layer - 1];
+    int rc = SDNN_OK;
+    if (d_values) rc = copy_dd(net, d_values, d.vals, 4 * (size_t)d.nnz, stream_);
+    if (!rc && d_bias) rc = copy_dd(net, d_bias, d.bias, 4 * (size_t)d.n_out, stream_);
+    return rc;
+}
+
+extern "C" int sdnn_set_weights(sdnn_net *net, int32_t layer, const float *d_values,
+                                const float *d_bias, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (layer < 1 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
+    const LayerDev &d = net->layers[layer - 1];
+    int rc = SDNN_OK;
+    if (d_values) rc = copy_dd(net, d.vals, d_values, 4 * (size_t)d.nnz, stream_);
+    if (!rc && d_bias) rc = copy_dd(net, d.bias, d_bias, 4 * (size_t)d.n_out, stream_);
+    return rc;
+}
+
+extern "C" int sdnn_layer_shape(const sdnn_net *net, int32_t layer, int32_t *n_out, int32_t *n_in,
+                                int64_t *nnz)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (layer < 1 || layer > net->n_layers) return fail(nullptr, SDNN_EINVAL, "layer out of range");
+    const LayerDev &d = net->layers[layer - 1];
+    if (n_out) *n_out = d.n_out;
+    if (n_in) *n_in = d.n_in;
+    if (nnz) *nnz = d.nnz;
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_mse_dloss(const float *d_XL, const float *d_Y, int32_t n, int32_t B,
+                              float *d_out, void *stream_)
+{
+    if (!d_XL || !d_Y || !d_out) return fail(nullptr, SDNN_EINVAL, "NULL pointer");
+    if (n < 0 || B < 1) return fail(nullptr, SDNN_EINVAL, "bad size");
+    const size_t cnt = (size_t)n * B;
+    if (!cnt) return SDNN_OK;
+    hipLaunchKernelGGL(k_mse_dloss, dim3(ew_blocks(cnt)), dim3(256), 0, (hipStream_t)stream_, d_XL,
+                       d_Y, d_out, cnt, (double)B);
+    HIP_TRY(nullptr, hipGetLastError());
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_softmax_ce_dloss(const float *d_XL, const int32_t *d_labels, int32_t n,
+                                     int32_t B, int32_t n_classes, float *d_out, void *stream_)
+{
+    if (!d_XL || !d_labels || !d_out) return fail(nullptr, SDNN_EINVAL, "NULL pointer");
+    if (n < 1 || B < 1 || n_classes < 1 || n_classes > n) return fail(nullptr, SDNN_EINVAL, "bad size");
+    const size_t cnt = std::max((size_t)(n - n_classes) * B, (size_t)B);
+    hipLaunchKernelGGL(k_softmax_ce_dloss, dim3(ew_blocks(cnt)), dim3(256), 0, (hipStream_t)stream_,
+                       d_XL, d_labels, d_out, n, B, n_classes);
+    HIP_TRY(nullptr, hipGetLastError());
+    return SDNN_OK;
+}

@@ -1,0 +1,26 @@
+// Shared between the translation units of libsdnn only.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+#include "../../include/sdnn.h"
+
+void sdnn_set_global_error(const char *fmt, ...);
+const char *sdnn_global_error();
+
+// Per-layer descriptor, readable by the kernels (a copy lives in the workspace).
+struct LayerDev {
+    int32_t n_out, n_in, nnz, pad_;
+    const int32_t *row_ptr;   // [n_out+1]
+    const int32_t *col_idx;   // [nnz]
+    float *vals;              // [nnz]
+    float *bias;              // [n_out]
+    const int32_t *t_row_ptr; // [n_in+1]   transposed index (rows of W^T = columns of W)
+    const int32_t *t_row_idx; // [nnz]
+    const int32_t *t_perm;    // [nnz]      position of the entry in vals
+    const int32_t *order;     // [n_out]    rows of W by decreasing length
+    const int32_t *t_order;   // [n_in]     rows of W^T by decreasing length
+    float *X_prev;            // X_{l-1}  [n_in][B]   (training mode)
+    float *X;                 // X_l      [n_out][B]  (training mode)
+    float *D;                 // Delta_l  [n_out][B]  (training mode)
+};

@@ -1,0 +1,179 @@
+"""GPU-vs-oracle parity through the C ABI, on seeded synthetic workloads.
+
+Bar: forward max relative error 1e-5 and identical active sets; deltas,
+gradients and updated weights within 1e-4 relative or 1e-6 absolute.  Since
+both sides accumulate exact fp32 x fp32 products in fp64 in the same order,
+the forward and backward results are in fact expected to be bit-identical and
+the tests say so where the kernel's summation order equals the oracle's.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2104_11805_amd import sdnn, workloads as wl
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("b", [1, 5, 64, 67, 130, 260])
+@pytest.mark.parametrize("cap", [float("inf"), 0.9])
+def test_tiny_rectangular_net_all_passes(b, cap):
+    work = wl.tiny_net(31, sizes=(37, 70, 33, 129, 20), density=0.3, b=b, cap=cap)
+    x0 = work.x_infer
+    g = P.gpu_train_step(work, x0, lr=0.05)
+    o = P.oracle_train_step(work, x0, lr=0.05)
+    st = P.compare_step(g, o, f"tiny b={b} cap={cap}")
+    assert st["live_d"] == st["layers"] and st["live_g"] == st["layers"]
+    assert st["bitexact_d"] == st["layers"]
+    for lay, (v, bias) in zip(work.layers, g["new"]):
+        assert (v != lay.values).any() and (bias != lay.bias).any()
+
+
+def test_empty_rows_empty_columns_and_zero_nnz_layer():
+    work = wl.tiny_net(32, sizes=(12, 40, 16, 9), density=0.08, b=7)
+    lens = [np.diff(l.row_ptr) for l in work.layers]
+    assert any((x == 0).any() for x in lens), "no empty row drawn"
+    # make the middle layer completely empty: its outputs are f(bias)
+    mid = work.layers[1]
+    mid.row_ptr = np.zeros_like(mid.row_ptr); mid.col_idx = mid.col_idx[:0]; mid.values = mid.values[:0]
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05)
+    P.compare_step(g, o, "empty")
+    assert g["new"][1][0].size == 0
+    assert (g["new"][1][1] != mid.bias).any(), "bias of a link-less neuron must still train"
+
+
+def test_live_config1_prefix_training_step():
+    """Depth-6 prefix of config 1 at input density 0.40: every mask open, dense
+    non-zero deltas and gradients in every layer."""
+    work = wl.make_config(1, n_layers=6, density=0.40)
+    g = P.gpu_train_step(work, work.x_train)
+    o = P.oracle_train_step(work, work.x_train)
+    st = P.compare_step(g, o, "cfg1-live")
+    assert st["live_d"] == 6 and st["live_g"] == 6 and st["bitexact_d"] == 6
+    for k in range(1, 7):
+        assert (o["deltas"][k] != 0).mean() > 0.9
+
+
+@pytest.mark.parametrize("density", [0.10, 0.30])
+def test_config1_full_depth(density):
+    """Config 1 verbatim (dead after layer 1 at density 0.10) and its live
+    forward companion at 0.30 (mixed transient, then saturated or dead)."""
+    work = wl.make_config(1, density=density)
+    g = P.gpu_train_step(work, work.x_train)
+    o = P.oracle_train_step(work, work.x_train)
+    st = P.compare_step(g, o, f"cfg1 d={density}")
+    frac = [float((x > 0).mean()) for x in o["xs"]]
+    if density == 0.10:
+        assert frac[1] > 0.1 and max(frac[2:]) == 0.0          # the degeneracy is visible
+        assert all((d == 0).all() for d in g["deltas"][1:])
+    else:
+        assert min(frac[1:8]) > 0.05 and any(0.0 < f < 1.0 for f in frac[3:12])
+    for lay, x in zip(work.layers, g["xs"][1:]):
+        assert (x >= 0).all() and (x <= 32).all()
+
+
+def test_irregular_net_scaled_config5():
+    """Heavy-tailed row degrees, mixed-sign weights, no cap, softmax-CE on the
+    last 10 neurons; gradients scaled by 2^12 so they clear the absolute floor."""
+    work = wl.make_config(5, n=1024, n_layers=5, b_infer=96, b_train=96)
+    lens = np.diff(work.layers[0].row_ptr)
+    assert lens.max() >= 20 * lens.min()
+    for scale in (1.0, 4096.0):
+        g = P.gpu_train_step(work, work.x_train, scale=scale)
+        o = P.oracle_train_step(work, work.x_train, scale=scale)
+        st = P.compare_step(g, o, f"cfg5-scaled x{scale}")
+        assert st["live_g"] == 5
+    assert max(np.abs(gr[0]).max() for gr in o["grads"]) > 1e-4
+
+
+def test_inference_mode_matches_training_forward_and_oracle():
+    work = wl.make_config(1, n=512, n_layers=7, b_infer=200, density=0.4)
+    x0 = P.dev(work.x_infer)
+    ref = P.O32.forward(work.layers, work.x_infer, work.act_cap)[-1]
+    for training in (False, True):
+        net = sdnn.Net(work.layers, work.act_cap, 256, training=training)
+        xl = torch.empty(512, 200, device=P.DEV)
+        net.sdnn_forward(x0, xl)
+        assert np.array_equal(P.host(xl), ref)
+        net.close()
+    # a block of the batch gives the same columns (samples are independent)
+    net = sdnn.Net(work.layers, work.act_cap, 256, training=False)
+    blk = torch.empty(512, 72, device=P.DEV)
+    net.sdnn_forward(P.dev(work.x_infer[:, 64:136]), blk)
+    assert np.array_equal(P.host(blk), ref[:, 64:136])
+    net.close()
+
+
+def test_two_runs_are_bit_identical():
+    work = wl.make_config(5, n=512, n_layers=4, b_infer=64, b_train=64)
+    a = P.gpu_train_step(work, work.x_train, scale=4096.0)
+    b = P.gpu_train_step(work, work.x_train, scale=4096.0)
+    for k in range(4):
+        assert np.array_equal(a["deltas"][k + 1], b["deltas"][k + 1])
+        assert np.array_equal(a["grads"][k][0], b["grads"][k][0])
+        assert np.array_equal(a["new"][k][0], b["new"][k][0])
+        assert np.array_equal(a["new"][k][1], b["new"][k][1])
+
+
+def test_update_options_and_pattern_confinement():
+    work = wl.tiny_net(33, sizes=(20, 30, 25), density=0.3, b=16)
+    base = P.gpu_train_step(work, work.x_infer, lr=0.0)
+    for lay, (v, b) in zip(work.layers, base["new"]):
+        assert np.array_equal(v, lay.values) and np.array_equal(b, lay.bias)   # lr = 0: untouched
+        assert v.size == lay.nnz                                               # pattern size fixed
+    frozen = P.gpu_train_step(work, work.x_infer, lr=0.05, update_bias=False)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05, update_bias=False)
+    for lay, (v, b), (ov, ob) in zip(work.layers, frozen["new"], o["new"]):
+        assert np.array_equal(b, lay.bias)
+        P.assert_grad_close(v, ov)
+
+
+def test_call_order_and_size_errors():
+    work = wl.tiny_net(34, sizes=(8, 10, 6), b=4)
+    net = sdnn.Net(work.layers, work.act_cap, 4, training=True)
+    x0 = P.dev(work.x_infer)
+    dl = torch.zeros(6, 4, device=P.DEV)
+    with pytest.raises(sdnn.SdnnError) as e:
+        net.sdnn_backward(dl)
+    assert e.value.code == sdnn.SDNN_ESTATE
+    with pytest.raises(sdnn.SdnnError) as e:
+        net.sdnn_sgd_step(0.1)
+    assert e.value.code == sdnn.SDNN_ESTATE
+    with pytest.raises(sdnn.SdnnError) as e:
+        net.sdnn_forward(torch.zeros(8, 5, device=P.DEV))
+    assert e.value.code == sdnn.SDNN_EINVAL
+    net.sdnn_forward(x0)
+    net.sdnn_backward(dl)
+    net.sdnn_sgd_step(0.1)
+    with pytest.raises(sdnn.SdnnError) as e:
+        net.sdnn_sgd_step(0.1)           # the backward pass was consumed
+    assert e.value.code == sdnn.SDNN_ESTATE
+    net.close()
+    inf = sdnn.Net(work.layers, work.act_cap, 4, training=False)
+    with pytest.raises(sdnn.SdnnError) as e:
+        inf.sdnn_forward(x0)             # inference needs an output buffer
+    assert e.value.code == sdnn.SDNN_EINVAL
+    out = torch.empty(6, 4, device=P.DEV)
+    inf.sdnn_forward(x0, out)
+    with pytest.raises(sdnn.SdnnError) as e:
+        inf.sdnn_backward(dl)
+    assert e.value.code == sdnn.SDNN_ESTATE
+    inf.close()
+
+
+def test_loss_gradient_kernels():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((40, 33)).astype(np.float32)
+    y = rng.random((40, 33)).astype(np.float32)
+    got = P.host(sdnn.sdnn_mse_dloss(P.dev(x), P.dev(y)))
+    assert np.array_equal(got, P.mse_dloss(x, y))
+    lab = rng.integers(0, 10, 33)
+    got = P.host(sdnn.sdnn_softmax_ce_dloss(P.dev(x), P.dev(lab, torch.int32), 10))
+    ref = P.softmax_ce_dloss(x, lab, 10)
+    assert (got[:30] == 0).all()
+    np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-9)
+    assert abs(got[30:].sum()) < 1e-6

@@ -1,0 +1,144 @@
+"""Host-side logic of libsdnn and the shape of its C ABI.  No GPU compute."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+from paper_2104_11805_amd import sdnn, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sdnn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sdnn_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 15
+    assert declared == set(sdnn.SIGNATURES), declared ^ set(sdnn.SIGNATURES)
+    l = sdnn.lib()
+    for name in declared:
+        assert hasattr(l, name), name
+    assert b"gfx950" in l.sdnn_version()
+
+
+def _csr(layer):
+    return layer.n_out, layer.n_in, layer.row_ptr, layer.col_idx
+
+
+def test_check_csr_accepts_generated_layers_and_rejects_malformed():
+    lay = wl.random_layer(3, 9, 7, 0.4)
+    assert sdnn.sdnn_check_csr(*_csr(lay)) == 0
+    bad = lay.col_idx.copy(); bad[1] = 7
+    assert sdnn.sdnn_check_csr(lay.n_out, lay.n_in, lay.row_ptr, bad) == sdnn.SDNN_EINVAL
+    assert "out of range" in sdnn.last_error()
+    r0 = next(j for j in range(lay.n_out) if lay.row_ptr[j + 1] - lay.row_ptr[j] >= 2)
+    dup = lay.col_idx.copy(); dup[lay.row_ptr[r0] + 1] = dup[lay.row_ptr[r0]]
+    assert sdnn.sdnn_check_csr(lay.n_out, lay.n_in, lay.row_ptr, dup) == sdnn.SDNN_EINVAL
+    assert "ascending" in sdnn.last_error()
+    rp = lay.row_ptr.copy(); rp[0] = 1
+    assert sdnn.sdnn_check_csr(lay.n_out, lay.n_in, rp, lay.col_idx) == sdnn.SDNN_EINVAL
+    rp = lay.row_ptr.copy(); rp[3] = rp[2] - 1
+    assert sdnn.sdnn_check_csr(lay.n_out, lay.n_in, rp, lay.col_idx) == sdnn.SDNN_EINVAL
+    assert sdnn.sdnn_check_csr(-1, 3, lay.row_ptr, lay.col_idx) == sdnn.SDNN_EINVAL
+    # empty matrix is fine
+    assert sdnn.sdnn_check_csr(0, 5, np.zeros(1, np.int32), np.zeros(0, np.int32)) == 0
+
+
+@pytest.mark.parametrize("shape", [(13, 9), (9, 13), (64, 64), (1, 5), (5, 1)])
+def test_transpose_pattern_against_scipy_and_involution(shape):
+    lay = wl.random_layer(17, shape[0], shape[1], 0.35)
+    t_rp, t_ri, t_pm = sdnn.sdnn_transpose_pattern(*_csr(lay))
+    nnz = lay.nnz
+    assert sorted(t_pm.tolist()) == list(range(nnz)), "perm is not a bijection"
+    tags = np.arange(1, nnz + 1, dtype=np.float64)
+    csc = sp.csr_matrix((tags, lay.col_idx, lay.row_ptr), shape=shape).tocsc()
+    csc.sort_indices()
+    np.testing.assert_array_equal(t_rp, csc.indptr)
+    np.testing.assert_array_equal(t_ri, csc.indices)
+    np.testing.assert_array_equal(t_pm, csc.data.astype(np.int64) - 1)
+    for i in range(shape[1]):
+        seg = t_ri[t_rp[i]:t_rp[i + 1]]
+        assert (np.diff(seg) > 0).all()
+        assert (lay.col_idx[t_pm[t_rp[i]:t_rp[i + 1]]] == i).all()
+    # transpose(transpose(W)) == W
+    b_rp, b_ri, b_pm = sdnn.sdnn_transpose_pattern(shape[1], shape[0], t_rp, t_ri)
+    np.testing.assert_array_equal(b_rp, lay.row_ptr)
+    np.testing.assert_array_equal(b_ri, lay.col_idx)
+    np.testing.assert_array_equal(t_pm[b_pm], np.arange(nnz))
+
+
+def test_transpose_of_benchmark_layer_counts_column_links():
+    lay = wl.regular_layer(1001, 1024, 32, 0.0625, -0.3)
+    t_rp, t_ri, t_pm = sdnn.sdnn_transpose_pattern(*_csr(lay))
+    np.testing.assert_array_equal(np.diff(t_rp), np.bincount(lay.col_idx, minlength=1024))
+    assert t_rp[-1] == lay.nnz == 32 * 1024
+
+
+def test_row_schedule_is_stable_longest_first():
+    lay = wl.irregular_layer(5, 256)
+    order = sdnn.sdnn_row_schedule(lay.n_out, lay.row_ptr)
+    lens = np.diff(lay.row_ptr)
+    assert sorted(order.tolist()) == list(range(256))
+    assert (np.diff(lens[order]) <= 0).all()
+    ties = lens[order][1:] == lens[order][:-1]
+    assert (np.diff(order)[ties] > 0).all()
+
+
+def _layer_array(layers):
+    keep, arr = [], (sdnn.sdnn_layer * len(layers))()
+    for k, l in enumerate(layers):
+        a = [np.ascontiguousarray(l.row_ptr, np.int32), np.ascontiguousarray(l.col_idx, np.int32),
+             np.ascontiguousarray(l.values, np.float32), np.ascontiguousarray(l.bias, np.float32)]
+        keep += a
+        arr[k] = sdnn.sdnn_layer(l.n_out, l.n_in, *[x.ctypes.data for x in a])
+    return arr, keep
+
+
+def test_workspace_bytes_and_argument_errors_without_gpu():
+    net = wl.tiny_net(1, sizes=(7, 9, 6, 8))
+    arr, keep = _layer_array(net.layers)
+    l = sdnn.lib()
+    n = C.c_size_t(0)
+    cfg = sdnn.sdnn_config(float("inf"), 16, 1, 1)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(cfg), C.byref(n)) == 0
+    train_bytes = n.value
+    nnz = sum(x.nnz for x in net.layers)
+    # CSR + transposed index (5 x 4 bytes per entry) + activations and deltas
+    assert train_bytes >= 20 * nnz + 4 * 16 * (2 * (9 + 6 + 8) + 7)
+    cfg_inf = sdnn.sdnn_config(float("inf"), 16, 0, 1)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(cfg_inf), C.byref(n)) == 0
+    assert 0 < n.value < train_bytes
+    # argument errors are reported before any GPU work
+    bad = sdnn.sdnn_config(float("inf"), 0, 1, 1)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
+    bad = sdnn.sdnn_config(0.0, 4, 1, 1)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
+    assert l.sdnn_workspace_bytes(arr, 0, C.byref(cfg), C.byref(n)) == sdnn.SDNN_EINVAL
+    h = C.c_void_p(1)
+    assert l.sdnn_create(arr, 3, C.byref(cfg), None, train_bytes, None, C.byref(h)) == sdnn.SDNN_EINVAL
+    assert h.value is None
+    assert l.sdnn_create(arr, 3, C.byref(cfg), C.c_void_p(4096 + 8), train_bytes, None, C.byref(h)) == sdnn.SDNN_EINVAL
+    assert "aligned" in sdnn.last_error()
+    assert l.sdnn_create(arr, 3, C.byref(cfg), C.c_void_p(4096), train_bytes - 1, None, C.byref(h)) == sdnn.SDNN_ENOMEM
+    # consecutive layers must chain
+    arr2, keep2 = _layer_array([net.layers[0], net.layers[2]])
+    assert l.sdnn_workspace_bytes(arr2, 2, C.byref(cfg), C.byref(n)) == sdnn.SDNN_EINVAL
+    # calls on a NULL net
+    assert l.sdnn_forward(None, None, 1, None, None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_backward(None, None, None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_sgd_step(None, 0.1, None) == sdnn.SDNN_EINVAL
+    l.sdnn_destroy(None)
+
+
+def test_malformed_layer_is_rejected_by_create_without_gpu():
+    net = wl.tiny_net(2, sizes=(7, 9, 6))
+    net.layers[1].col_idx = net.layers[1].col_idx.copy()
+    net.layers[1].col_idx[0] = 99
+    arr, keep = _layer_array(net.layers)
+    cfg = sdnn.sdnn_config(32.0, 4, 1, 1)
+    h = C.c_void_p()
+    assert sdnn.lib().sdnn_create(arr, 2, C.byref(cfg), C.c_void_p(4096), 1 << 30, None, C.byref(h)) == sdnn.SDNN_EINVAL
+    assert "layer 2" in sdnn.last_error()

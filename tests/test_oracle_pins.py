@@ -280,3 +280,15 @@ def test_backward_samples_are_independent_bitwise():
     for k in range(1, len(full)):
         assert np.array_equal(full[k][:, s], one[k][:, 0])
         assert (full[k] != 0).any()
+
+
+def test_cap_is_a_number_of_the_storage_precision():
+    """A neuron clamped at a cap that fp32 cannot represent exactly (0.9) must
+    still read as saturated (derivative 0) from its stored fp32 output."""
+    lay = wl.random_layer(1, 4, 4, 1.0)
+    lay.values = np.full(lay.nnz, 1.0, np.float32)
+    lay.bias = np.zeros(4, np.float32)
+    x1 = O32.forward_layer(lay, np.ones((4, 1), np.float32), 0.9)
+    assert (x1 == np.float32(0.9)).all()
+    d = O32.output_delta(np.ones((4, 1), np.float32), x1, 0.9)
+    assert (d == 0).all()
