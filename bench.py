@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-DNN SGD hot path on one MI355X.
+
+A step = one pass of the whole hot path on one training minibatch, through the
+C ABI: sdnn_forward, loss gradient, sdnn_backward, sdnn_sgd_step.  Throughput
+is edges/s = (sum of nnz over the layers) x samples / seconds, the throughput
+definition of the paper's inference table (Section 6.4), applied to the full
+training step and, in a second figure, to the inference forward pass.
+
+Prints ONE JSON line.  Inputs are resident in HBM before the timed region.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def layer_bytes(n, nnz, b):
+    """Algorithmic HBM bytes of one launch per layer (each array moved once)."""
+    act = 4 * n * b
+    fwd = 8 * nnz + 4 * (n + 1) + 4 * n + 2 * act                 # W, row_ptr, bias, X in, X out
+    bwd = 12 * nnz + 4 * (n + 1) + 3 * act                          # index+perm, values, D in, X mask, D out
+    upd = 8 * nnz + 4 * nnz + 4 * (n + 1) + 8 * n + 2 * act         # W r/w, bias r/w, D, X
+    return fwd, bwd, upd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
+    ap.add_argument("--layers", type=int, default=None, help="depth prefix (default: full depth)")
+    ap.add_argument("--density", type=float, default=None, help="input density override (live inputs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-inference", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2104_11805_amd import sdnn, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    t0 = time.time()
+    work = wl.make_config(args.config, n_layers=args.layers, density=args.density)
+    N, L, nnz_total = work.n, len(work.layers), work.total_nnz
+    Bt, Bi = work.train_batch, work.x_infer.shape[1]
+    gen_s = time.time() - t0
+
+    def to_dev(a, dtype=None):
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        return (t.to(dtype) if dtype is not None else t).to(dev)
+
+    # ---- training step --------------------------------------------------
+    net = sdnn.Net(work.layers, work.act_cap, Bt, training=True)
+    x0 = to_dev(work.x_train)
+    xl = torch.empty(work.layers[-1].n_out, Bt, device=dev)
+    dl = torch.empty_like(xl)
+    if work.loss == "mse":
+        y = to_dev(work.targets)
+        loss_grad = lambda: sdnn.sdnn_mse_dloss(xl, y, out=dl)
+    else:
+        lab = to_dev(work.labels, torch.int32)
+        loss_grad = lambda: sdnn.sdnn_softmax_ce_dloss(xl, lab, work.n_classes, out=dl)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record=False):
+        e = [ev() for _ in range(4)] if record else None
+        if record: e[0].record()
+        net.sdnn_forward(x0, xl)
+        if record: e[1].record()
+        loss_grad()
+        net.sdnn_backward(dl)
+        if record: e[2].record()
+        net.sdnn_sgd_step(work.lr)
+        if record: e[3].record()
+        if record: marks.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(record=True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in marks) / len(marks)
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in marks) / len(marks)
+    upd_ms = sum(e[2].elapsed_time(e[3]) for e in marks) / len(marks)
+    train_eps = nnz_total * Bt / (ms_step * 1e-3)
+
+    # ---- roofline of the dominant kernel --------------------------------
+    fb = bb = ub = 0
+    for lay in work.layers:
+        f, b, u = layer_bytes(lay.n_out, lay.nnz, Bt)
+        fb += f; bb += b; ub += u
+    passes = {"forward": (fwd_ms, fb, L), "backward": (bwd_ms, bb - layer_bytes(N, work.layers[0].nnz, Bt)[1], L - 1),
+              "update": (upd_ms, ub, 1)}
+    dom = max(passes, key=lambda k: passes[k][0])
+    d_ms, d_bytes, d_launches = passes[dom]
+    achieved = d_bytes / (d_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "launches_per_step": d_launches, "avg_launch_us": round(d_ms * 1e3 / d_launches, 3),
+                "bytes_per_launch": int(d_bytes / d_launches)}
+    net.close()
+    del net
+
+    # ---- inference forward over the full sample set ----------------------
+    infer = None
+    if not args.no_inference:
+        block = min(Bi, 1024 if N >= 65536 else Bi)
+        inet = sdnn.Net(work.layers, work.act_cap, block, training=False)
+        xi = to_dev(work.x_infer)
+        blocks = [(s, min(block, Bi - s)) for s in range(0, Bi, block)]
+        xin = [xi[:, s:s + w].contiguous() for s, w in blocks]
+        xout = [torch.empty(work.layers[-1].n_out, w, device=dev) for s, w in blocks]
+
+        def infer_pass():
+            for a, o in zip(xin, xout):
+                inet.sdnn_forward(a, o)
+
+        for _ in range(max(1, args.warmup)):
+            infer_pass()
+        torch.cuda.synchronize()
+        k = max(3, args.steps // 2)
+        t0 = time.perf_counter()
+        for _ in range(k):
+            infer_pass()
+        torch.cuda.synchronize()
+        ims = (time.perf_counter() - t0) * 1e3 / k
+        ibytes = sum(layer_bytes(l.n_out, l.nnz, Bi)[0] for l in work.layers)
+        infer = {"edges_per_s": nnz_total * Bi / (ims * 1e-3), "ms": round(ims, 3), "samples": Bi,
+                 "block": block, "algorithmic_GBs": round(ibytes / (ims * 1e-3) / 1e9, 1),
+                 "hbm_frac": round(ibytes / (ims * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        inet.close()
+        del inet
+
+    # ---- the oracle on the host cores, as a baseline ----------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.sdnn_oracle import Oracle, mse_dloss, softmax_ce_dloss
+        orc = Oracle(np.float32)
+        if work.loss == "mse":
+            dfn = lambda x: mse_dloss(x, work.targets)
+        else:
+            dfn = lambda x: softmax_ce_dloss(x, work.labels, work.n_classes)
+        t0 = time.perf_counter()
+        orc.train_step(work.layers, work.x_train, work.act_cap, dfn, work.lr)
+        cs = time.perf_counter() - t0
+        cpu = {"value": nnz_total * Bt / cs, "unit": "edges/s", "cores": orc.threads(), "kind": "oracle",
+               "sample": f"one full training step: all {L} layers, minibatch {Bt} ({cs:.1f} s)"}
+
+    out = {
+        "metric": "edges/s, forward+backward+SGD step (nnz x samples / time)",
+        "value": train_eps, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: N={N}, L={L}, 32 nnz/row" if args.config < 5
+                   else f"config 5: N={N}, L={L}, heavy-tailed rows",
+                   "train_batch": Bt, "infer_samples": Bi, "total_nnz": nnz_total,
+                   "storage": "fp32", "accumulate": "fp64", "input_density": work.meta.get("density")},
+        "pass_ms": {"forward": round(fwd_ms, 4), "backward": round(bwd_ms, 4), "update": round(upd_ms, 4)},
+        "inference": infer, "roofline": roofline, "cpu_baseline": cpu,
+        "setup_s": {"generate": round(gen_s, 2)},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

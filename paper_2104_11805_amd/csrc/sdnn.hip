@@ -55,6 +55,33 @@ template <> __device__ __forceinline__ void stv<4>(float *p, const float (&x)[4]
     *reinterpret_cast<float4 *>(p) = make_float4(x[0], x[1], x[2], x[3]);
 }
 
+// Gather of V consecutive floats of an activation row through a buffer
+// descriptor: the address is (uniform base) + (scalar row offset) + (lane
+// offset), so a load costs one SGPR and no per-load address VGPRs.  Offsets are
+// 32-bit byte offsets: an activation block must stay below 4 GiB (checked by the
+// host).  Reads past num_records return 0 instead of faulting.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const float *base, size_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)(unsigned)bytes, 0x00020000);
+}
+template <int V>
+__device__ __forceinline__ void gatherv(__amdgpu_buffer_rsrc_t r, unsigned lane_off, unsigned row_off,
+                                        float (&x)[V])
+{
+    if constexpr (V == 1) {
+        x[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)row_off, 0));
+    } else if constexpr (V == 2) {
+        const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, 0);
+        x[0] = __uint_as_float(t.x); x[1] = __uint_as_float(t.y);
+    } else {
+        const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)row_off, 0);
+        x[0] = __uint_as_float(t.x); x[1] = __uint_as_float(t.y);
+        x[2] = __uint_as_float(t.z); x[3] = __uint_as_float(t.w);
+    }
+}
+
 // Workgroup ids are handed to the 8 XCDs round-robin and each XCD has its own
 // L2.  Give every XCD whole batch tiles (all row groups of tile x, x+8, ...)
 // so that the activation slab of a tile is gathered through one L2 only.  The
@@ -88,12 +115,134 @@ struct SpmmArgs {
     const int32_t *perm;  // MODE 1 only
     const int32_t *order; // rows by decreasing length
     const float *in;      // [n_cols][B]
+    size_t in_bytes;      // < 4 GiB
     float *out;           // [n_rows][B]
     const float *aux;     // MODE 0: bias [n_rows] (may be NULL); MODE 1: Xprev [n_rows][B]
     int32_t n_rows, B;
     uint32_t n_tiles, n_rg;
     float cap;
 };
+
+// The part of a row task that does not depend on the previous layer's output:
+// which row, where its entries are, and its first (up to) 64 entries, entry k
+// held by lane k.
+struct RowMeta {
+    int row, beg, end;
+    int c_l;
+    float w_l;
+};
+
+template <int MODE>
+__device__ __forceinline__ void load_chunk(const int32_t *idx, const float *vals, const int32_t *perm,
+                                           int base, int end, int lane, int &c_l, float &w_l)
+{
+    c_l = 0;
+    w_l = 0.0f;
+    if (base + lane < end) {
+        c_l = idx[base + lane];
+        w_l = MODE == 1 ? vals[perm[base + lane]] : vals[base + lane];
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ RowMeta load_meta(const int32_t *order, const int32_t *row_ptr,
+                                             const int32_t *idx, const float *vals,
+                                             const int32_t *perm, int r, int lane)
+{
+    RowMeta m;
+    m.row = order[r];
+    m.beg = row_ptr[m.row];
+    m.end = row_ptr[m.row + 1];
+    load_chunk<MODE>(idx, vals, perm, m.beg, m.end, lane, m.c_l, m.w_l);
+    return m;
+}
+
+// One row of the product for the 64*V samples of one batch tile.  All 64 lanes
+// must be active (lane k's registers are read by readlane); lanes past the end
+// of the batch redo sample 0 and do not store.
+template <int V, int MODE>
+__device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const float *vals,
+                                         const int32_t *perm, const float *in, size_t in_bytes,
+                                         float *out, const float *aux, int B, float capf,
+                                         unsigned tile, int lane)
+{
+    const int s_own = (int)tile * (64 * V) + lane * V;
+    const bool live = s_own < B;
+    const int s = live ? s_own : 0;
+    const size_t ld = (size_t)B;
+    const unsigned so = 4u * (unsigned)s;  // byte offset of the lane inside an activation row
+    const unsigned ldb = 4u * (unsigned)B; // bytes per activation row
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, in_bytes);
+
+    // operands of the epilogue, requested early so that they arrive with the gathers
+    float xp[V];
+    double b = 0.0;
+    if (MODE == 0) {
+        if (aux) b = (double)aux[m.row];
+    } else {
+        ldv<V>(aux + (size_t)m.row * ld + s, xp);
+    }
+
+    double acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+
+    // U gathers are in flight per lane before the first of them is consumed
+    constexpr int U = 16;
+    int c_l = m.c_l;
+    float w_l = m.w_l;
+    for (int base = m.beg; base < m.end; base += 64) {
+        const int n = min(64, m.end - base);
+        if (base != m.beg) load_chunk<MODE>(idx, vals, perm, base, m.end, lane, c_l, w_l);
+        for (int g = 0; g < n; g += U) {
+            float x[U][V];
+            if (g + U <= n) {
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    const int c = __builtin_amdgcn_readlane(c_l, g + k);
+                    gatherv<V>(rin, so, (unsigned)c * ldb, x[k]);
+                }
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    const double wk = (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_l), g + k));
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+                }
+            } else {
+                // ragged end of the row: same order, every entry guarded (wave-uniform branches)
+#pragma unroll
+                for (int k = 0; k < U; ++k)
+                    if (g + k < n) {
+                        const int c = __builtin_amdgcn_readlane(c_l, g + k);
+                        gatherv<V>(rin, so, (unsigned)c * ldb, x[k]);
+                    }
+#pragma unroll
+                for (int k = 0; k < U; ++k)
+                    if (g + k < n) {
+                        const double wk = (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_l), g + k));
+#pragma unroll
+                        for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+                    }
+            }
+        }
+    }
+
+    float o[V];
+    const double cap = (double)capf;
+    if (MODE == 0) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            double z = acc[v] + b;
+            z = z < 0.0 ? 0.0 : z;
+            z = z > cap ? cap : z;
+            o[v] = (float)z;
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) o[v] = (xp[v] > 0.0f && xp[v] < capf) ? (float)acc[v] : 0.0f;
+    }
+    if (live) stv<V>(out + (size_t)m.row * ld + s, o);
+}
 
 template <int V, int MODE>
 __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
@@ -103,62 +252,8 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
     map_block(blockIdx.x, a.n_tiles, a.n_rg, tile, rg);
     const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
     if (r >= a.n_rows) return;
-    const int s = (int)tile * (64 * V) + lane * V;
-    if (s >= a.B) return;
-    const int row = a.order[r];
-    const int beg = a.row_ptr[row], end = a.row_ptr[row + 1];
-    const size_t ld = (size_t)a.B;
-    const float *in = a.in + s;
-
-    double acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.0;
-
-    constexpr int U = 8;
-    int p = beg;
-    for (; p + U <= end; p += U) {
-        float w[U];
-        float x[U][V];
-#pragma unroll
-        for (int k = 0; k < U; ++k) {
-            const int c = a.idx[p + k];
-            w[k] = MODE == 1 ? a.vals[a.perm[p + k]] : a.vals[p + k];
-            ldv<V>(in + (size_t)c * ld, x[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < U; ++k) {
-            const double wk = (double)w[k];
-#pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
-        }
-    }
-    for (; p < end; ++p) {
-        const int c = a.idx[p];
-        const double wk = (double)(MODE == 1 ? a.vals[a.perm[p]] : a.vals[p]);
-        float x[V];
-        ldv<V>(in + (size_t)c * ld, x);
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[v], acc[v]);
-    }
-
-    float o[V];
-    const double cap = (double)a.cap;
-    if (MODE == 0) {
-        const double b = a.aux ? (double)a.aux[row] : 0.0;
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            double z = acc[v] + b;
-            z = z < 0.0 ? 0.0 : z;
-            z = z > cap ? cap : z;
-            o[v] = (float)z;
-        }
-    } else {
-        float xp[V];
-        ldv<V>(a.aux + (size_t)row * ld + s, xp);
-#pragma unroll
-        for (int v = 0; v < V; ++v) o[v] = (xp[v] > 0.0f && xp[v] < a.cap) ? (float)acc[v] : 0.0f;
-    }
-    stv<V>(a.out + (size_t)row * ld + s, o);
+    const RowMeta m = load_meta<MODE>(a.order, a.row_ptr, a.idx, a.vals, a.perm, r, lane);
+    spmm_row<V, MODE>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, tile, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -245,15 +340,25 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int B, float lr, int u
 #pragma unroll
                 for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
         }
-        // 16-lane transpose-reduce: 8 values/lane -> 1 value/lane
+        // 16-lane transpose-reduce: 8 values/lane -> 1 value/lane (register indices are compile-time)
+        {
+            const bool up8 = (lane & 8) != 0, up4 = (lane & 4) != 0, up2 = (lane & 2) != 0;
 #pragma unroll
-        for (int half = 4, bit = 8; half >= 1; half >>= 1, bit >>= 1) {
-            const bool up = (lane & bit) != 0;
+            for (int j = 0; j < 4; ++j) {
+                const double send = up8 ? a[j] : a[j + 4];
+                const double keep = up8 ? a[j + 4] : a[j];
+                a[j] = keep + __shfl_xor(send, 8);
+            }
 #pragma unroll
-            for (int j = 0; j < half; ++j) {
-                const double send = up ? a[j] : a[j + half];
-                const double keep = up ? a[j + half] : a[j];
-                a[j] = keep + __shfl_xor(send, bit);
+            for (int j = 0; j < 2; ++j) {
+                const double send = up4 ? a[j] : a[j + 2];
+                const double keep = up4 ? a[j + 2] : a[j];
+                a[j] = keep + __shfl_xor(send, 4);
+            }
+            {
+                const double send = up2 ? a[0] : a[1];
+                const double keep = up2 ? a[1] : a[0];
+                a[0] = keep + __shfl_xor(send, 2);
             }
         }
         a[0] += __shfl_xor(a[0], 1);
@@ -553,6 +658,9 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     }
     a.vals = d.vals; a.in = in; a.out = out; a.aux = aux; a.B = B; a.cap = net->cfg.act_cap;
     if (a.n_rows == 0) return SDNN_OK;
+    a.in_bytes = 4 * (size_t)(MODE == 0 ? d.n_in : d.n_out) * (size_t)B;
+    if (a.in_bytes >= ((size_t)1 << 32))
+        return fail(net, SDNN_EINVAL, "activation block of %zu bytes exceeds 4 GiB: use a smaller B", a.in_bytes);
     const int V = pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
     a.n_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
