@@ -119,7 +119,7 @@ struct SpmmArgs {
     float *out;           // [n_rows][B]
     const float *aux;     // MODE 0: bias [n_rows] (may be NULL); MODE 1: Xprev [n_rows][B]
     int32_t n_rows, B;
-    uint32_t n_tiles, n_rg;
+    uint32_t n_tiles, n_rg, n_vblocks;
     float cap;
 };
 
@@ -160,7 +160,7 @@ __device__ __forceinline__ RowMeta load_meta(const int32_t *order, const int32_t
 // One row of the product for the 64*V samples of one batch tile.  All 64 lanes
 // must be active (lane k's registers are read by readlane); lanes past the end
 // of the batch redo sample 0 and do not store.
-template <int V, int MODE>
+template <int V, int MODE, int U>
 __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const float *vals,
                                          const int32_t *perm, const float *in, size_t in_bytes,
                                          float *out, const float *aux, int B, float capf,
@@ -188,7 +188,6 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
 
     // U gathers are in flight per lane before the first of them is consumed
-    constexpr int U = 16;
     int c_l = m.c_l;
     float w_l = m.w_l;
     for (int base = m.beg; base < m.end; base += 64) {
@@ -244,16 +243,23 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
     if (live) stv<V>(out + (size_t)m.row * ld + s, o);
 }
 
-template <int V, int MODE>
+// The grid is sized to what the chip holds at once and every workgroup walks
+// "virtual blocks" blockIdx.x, blockIdx.x + gridDim.x, ...: a wavefront that
+// handles one short row and exits costs more to dispatch than to run.
+// gridDim.x is a multiple of 8, so a workgroup keeps its XCD's tiles.
+template <int V, int MODE, int U>
 __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
 {
     const int lane = threadIdx.x & 63;
-    unsigned tile, rg;
-    map_block(blockIdx.x, a.n_tiles, a.n_rg, tile, rg);
-    const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
-    if (r >= a.n_rows) return;
-    const RowMeta m = load_meta<MODE>(a.order, a.row_ptr, a.idx, a.vals, a.perm, r, lane);
-    spmm_row<V, MODE>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, tile, lane);
+    const unsigned wave = threadIdx.x >> 6;
+    for (unsigned vb = blockIdx.x; vb < a.n_vblocks; vb += gridDim.x) {
+        unsigned tile, rg;
+        map_block(vb, a.n_tiles, a.n_rg, tile, rg);
+        const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
+        if (r >= a.n_rows) continue;
+        const RowMeta m = load_meta<MODE>(a.order, a.row_ptr, a.idx, a.vals, a.perm, r, lane);
+        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, tile, lane);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -281,65 +287,84 @@ __global__ void __launch_bounds__(256) k_output_delta(const float *__restrict__ 
 // ---------------------------------------------------------------------------
 template <int V>
 __global__ void __launch_bounds__(BLOCK_THREADS)
-k_update(const LayerDev *__restrict__ layers, int layer0, int B, float lr, int update_bias,
+k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, unsigned n_rg, int B, float lr,
+         int update_bias,
          int emit, float *__restrict__ g_out, float *__restrict__ gb_out)
 {
-    const LayerDev &L = layers[layer0 + blockIdx.y];
+    // Workgroup ids are dealt to the 8 XCDs round-robin.  Eight consecutive layers are interleaved
+    // so that XCD x works on layer 8q + x: all gathers of one layer go through one L2, which then
+    // fetches that layer's activations once instead of once per XCD.
+    const unsigned lgroup = blockIdx.x / (8u * n_rg), within = blockIdx.x % (8u * n_rg);
+    const int layer_rel = (int)(8u * lgroup + (within & 7u));
+    if (layer_rel >= n_layers) return;
+    const LayerDev &L = layers[layer0 + layer_rel];
     const int lane = threadIdx.x & 63;
-    const int r = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
+    const int r = __builtin_amdgcn_readfirstlane((int)((within >> 3) * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
     if (r >= L.n_out) return;
     const int row = L.order[r];
     const int beg = L.row_ptr[row], end = L.row_ptr[row + 1];
-    const size_t ld = (size_t)B;
-    const float *drow = L.D + (size_t)row * ld;
-    const float *xp = L.X_prev;
+    const unsigned ldb = 4u * (unsigned)B;
     const double dlr = (double)lr;
-
-    // bias gradient: sum of the row of Delta over the samples
-    if (emit ? gb_out != nullptr : update_bias != 0) {
-        double sum = 0.0;
-        for (int s = lane * V; s < B; s += 64 * V) {
-            float d[V];
-            ldv<V>(drow + s, d);
-#pragma unroll
-            for (int v = 0; v < V; ++v) sum += (double)d[v];
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-        if (lane == 0) {
-            const float gb = (float)sum;
-            if (emit) gb_out[row] = gb;
-            else L.bias[row] = (float)((double)L.bias[row] - dlr * (double)gb);
-        }
-    }
-    if (emit && g_out == nullptr) return;
-
+    const bool want_bias = emit ? gb_out != nullptr : update_bias != 0;
+    const bool want_g = !(emit && g_out == nullptr);
     const int sg = lane & 15, eg = lane >> 4;
-    for (int base = beg; base < end; base += 32) {
+    const unsigned so = 4u * (unsigned)(sg * V); // byte offset of this lane's first sample
+    // descriptors: the Delta row of this matrix row, and the whole X_{l-1} block (reads past the end give 0)
+    const __amdgpu_buffer_rsrc_t rd = make_rsrc(L.D + (size_t)row * B, ldb);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(L.X_prev, (size_t)L.n_in * ldb);
+    const int n_pass = (B + 16 * V - 1) / (16 * V);
+
+    double bsum = 0.0;
+    bool first_chunk = true;
+    for (int base = beg; base < end || (first_chunk && want_bias); base += 32) {
         const int p0 = base + eg * 8;
-        size_t coff[8];
+        unsigned coff[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int p = p0 + k;
-            coff[k] = (size_t)(p < end ? L.col_idx[p] : L.col_idx[beg]) * ld;
+            // slots past the end of the row re-read the row's first entry; their sums are dropped
+            coff[k] = (p < end ? (unsigned)L.col_idx[p] : (beg < end ? (unsigned)L.col_idx[beg] : 0u)) * ldb + so;
         }
         double a[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = 0.0;
-        for (int s = sg * V; s < B; s += 16 * V) {
-            float df[V];
-            ldv<V>(drow + s, df);
-            float x[8][V];
+        if (want_g || first_chunk) {
+            for (int t = 0; t < n_pass; ++t) {
+                const unsigned po = (unsigned)t * (64u * V); // byte offset of pass t inside a row (scalar)
+                float df[V];
+                gatherv<V>(rd, so + po, 0u, df); // lanes past the end of the batch read 0 (range-checked offset)
+                float x[8][V];
+                if (want_g && base < end) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) ldv<V>(xp + coff[k] + s, x[k]);
-            double d[V];
+                    for (int k = 0; k < 8; ++k) gatherv<V>(rx, coff[k], po, x[k]);
+                }
+                double d[V];
 #pragma unroll
-            for (int v = 0; v < V; ++v) d[v] = (double)df[v];
+                for (int v = 0; v < V; ++v) d[v] = (double)df[v];
+                if (first_chunk) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
+                    for (int v = 0; v < V; ++v) bsum += d[v];
+                }
+                if (want_g && base < end) {
 #pragma unroll
-                for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
+                    for (int k = 0; k < 8; ++k)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
+                }
+            }
         }
+        if (first_chunk && want_bias) {
+            // bias gradient: sum of the Delta row over the samples (the 16 sample lanes of edge group 0)
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) bsum += __shfl_xor(bsum, off);
+            if (lane == 0) {
+                const float gb = (float)bsum;
+                if (emit) gb_out[row] = gb;
+                else L.bias[row] = (float)((double)L.bias[row] - dlr * (double)gb);
+            }
+        }
+        first_chunk = false;
+        if (!want_g || base >= end) break;
         // 16-lane transpose-reduce: 8 values/lane -> 1 value/lane (register indices are compile-time)
         {
             const bool up8 = (lane & 8) != 0, up4 = (lane & 4) != 0, up2 = (lane & 2) != 0;
@@ -420,6 +445,8 @@ struct sdnn_net {
     LayerDev *d_layers = nullptr; // device copy
     float *d_x0 = nullptr;        // training: X_0 [n_in(1)][max_batch]
     float *d_ping = nullptr, *d_pong = nullptr; // inference: two activation buffers
+    int n_cu = 0;                 // compute units of the device
+    int occ_spmm[2][3] = {{0, 0, 0}, {0, 0, 0}}; // resident workgroups per CU of k_spmm<V,MODE>
     int state = ST_IDLE;
     int32_t B = 0;
     int32_t max_n = 0;
@@ -621,6 +648,13 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     net->d_layers = (LayerDev *)(base + pl.table);
     UP(net->d_layers, net->layers.data(), sizeof(LayerDev) * (size_t)n_layers);
 #undef UP
+    {
+        int devid = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&devid) != hipSuccess || hipGetDeviceProperties(&prop, devid) != hipSuccess)
+            return fail_free(fail(nullptr, SDNN_EHIP, "cannot query the device"));
+        net->n_cu = prop.multiProcessorCount;
+    }
     if (cfg->training) {
         net->d_x0 = (float *)(base + pl.x0);
     } else {
@@ -666,10 +700,19 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     const uint64_t blocks = (uint64_t)a.n_tiles * a.n_rg;
     if (blocks > 0x7fffffffull) return fail(net, SDNN_EINVAL, "grid too large");
-    dim3 grid((unsigned)blocks), block(BLOCK_THREADS);
-    if (V == 4) hipLaunchKernelGGL((k_spmm<4, MODE>), grid, block, 0, stream, a);
-    else if (V == 2) hipLaunchKernelGGL((k_spmm<2, MODE>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((k_spmm<1, MODE>), grid, block, 0, stream, a);
+    a.n_vblocks = (uint32_t)blocks;
+    // 8 gathers in flight per lane measured best (16 costs a third of the occupancy, 4 exposes latency)
+    const void *fn = V == 4 ? (const void *)k_spmm<4, MODE, 8> : V == 2 ? (const void *)k_spmm<2, MODE, 8>
+                                                                      : (const void *)k_spmm<1, MODE, 8>;
+    int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0];
+    if (per_cu == 0) {
+        HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BLOCK_THREADS, 0));
+        if (per_cu < 1) per_cu = 1;
+    }
+    uint64_t g = std::min(blocks, (uint64_t)per_cu * (uint64_t)net->n_cu);
+    if (g >= 8) g &= ~(uint64_t)7; // keeps virtual block id % 8 == workgroup id % 8 (XCD-wise tiles)
+    void *args[] = {(void *)&a};
+    HIP_TRY(net, hipLaunchKernel(fn, dim3((unsigned)g), dim3(BLOCK_THREADS), args, 0, stream));
     HIP_TRY(net, hipGetLastError());
     return SDNN_OK;
 }
@@ -753,15 +796,19 @@ static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int 
     const int B = net->B;
     // all activation / delta buffers are 256-byte aligned; rows are aligned iff B % 4 == 0
     const int V = pick_v_update(B, net->layers[layer0].D, net->layers[layer0].X_prev);
-    for (int l0 = 0; l0 < n_layers; l0 += 65535) {
-        const int nl = std::min(65535, n_layers - l0);
-        dim3 grid((unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), (unsigned)nl);
+    // grid.x enumerates (group of 8 layers, row group, layer inside the group)
+    const uint64_t n_rg = (uint64_t)(max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const uint64_t per_group = 8 * n_rg;
+    const int groups_per_launch = (int)std::max<uint64_t>(1, std::min<uint64_t>(0x7fffffffull / per_group, 1u << 20));
+    for (int l0 = 0; l0 < n_layers; l0 += 8 * groups_per_launch) {
+        const int nl = std::min(8 * groups_per_launch, n_layers - l0);
+        dim3 grid((unsigned)(per_group * (uint64_t)((nl + 7) / 8)));
         if (V == 4)
             hipLaunchKernelGGL(k_update<4>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
-                               layer0 + l0, B, lr, net->cfg.update_bias, emit, g, gb);
+                               layer0 + l0, nl, (unsigned)n_rg, B, lr, net->cfg.update_bias, emit, g, gb);
         else
             hipLaunchKernelGGL(k_update<1>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
-                               layer0 + l0, B, lr, net->cfg.update_bias, emit, g, gb);
+                               layer0 + l0, nl, (unsigned)n_rg, B, lr, net->cfg.update_bias, emit, g, gb);
         HIP_TRY(net, hipGetLastError());
     }
     return SDNN_OK;
