@@ -114,8 +114,17 @@ def main():
     dom = max(passes, key=lambda k: passes[k][0])
     d_ms, d_bytes, d_launches = passes[dom]
     achieved = d_bytes / (d_ms * 1e-3) / 1e9
+    # measured HBM-side bytes per launch of that kernel (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the
+    # copy-kernel calibration), taken from the committed counter summary of this same workload
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"config{args.config}_traffic.json")
+    if os.path.exists(tpath) and args.layers is None and args.density is None:
+        t = json.load(open(tpath))
+        k = t["kernels"][dom]
+        traffic = int(1024 * (k["fetch_KiB"] * t["scale"]["FETCH_SIZE"] + k["write_KiB"] * t["scale"]["WRITE_SIZE"]))
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "binding_unit": "vector L1 gather path (~30 B/clk/CU, see profiles/config2_counters.md)",
                 "launches_per_step": d_launches, "avg_launch_us": round(d_ms * 1e3 / d_launches, 3),
                 "bytes_per_launch": int(d_bytes / d_launches)}
     net.close()
