@@ -41,15 +41,22 @@ int FN(oracle_threads)(void) { return omp_get_max_threads(); }
 int FN(oracle_threads)(void) { return 1; }
 #endif
 
-/* Activation f(z) = min(max(z, 0), cap); cap = +inf gives plain ReLU.
- * Its derivative is 1 strictly inside (0, cap) and 0 elsewhere, and is
- * evaluated from the stored output x = f(z): 0 < x < cap  <=>  0 < z < cap. */
-static inline double act(double z, double cap) {
+#include <math.h>
+
+/* Two activations (Section 4.1 names "ReLu, sigmoid etc."; the paper's training
+ * experiments use the sigmoid, Section 6.1):
+ *   kind 0: f(z) = min(max(z, 0), cap); cap = +inf gives plain ReLU.  f' is 1
+ *           strictly inside (0, cap) and 0 elsewhere, evaluated from the stored
+ *           output x = f(z): 0 < x < cap  <=>  0 < z < cap.
+ *   kind 1: f(z) = 1 / (1 + exp(-z));  f'(z) = x (1 - x) from the stored x. */
+static inline double act(int kind, double z, double cap) {
+    if (kind == 1) return 1.0 / (1.0 + exp(-z));
     if (z < 0.0) z = 0.0;
     if (z > cap) z = cap;
     return z;
 }
-static inline double act_deriv_from_output(double x, double cap) {
+static inline double act_deriv_from_output(int kind, double x, double cap) {
+    if (kind == 1) return x * (1.0 - x);
     return (x > 0.0 && x < cap) ? 1.0 : 0.0;
 }
 
@@ -57,7 +64,7 @@ static inline double act_deriv_from_output(double x, double cap) {
  * z(j,s) = sum over the stored entries of row j, in storage order. */
 void FN(oracle_forward_layer)(int32_t n_out, const int32_t *row_ptr, const int32_t *col_idx,
                               const REAL *vals, const REAL *bias, const REAL *Xin, int32_t B,
-                              double cap, REAL *Xout)
+                              int kind, double cap, REAL *Xout)
 {
 #pragma omp parallel for schedule(dynamic, 16)
     for (int32_t j = 0; j < n_out; ++j) {
@@ -66,17 +73,17 @@ void FN(oracle_forward_layer)(int32_t n_out, const int32_t *row_ptr, const int32
             for (int32_t p = row_ptr[j]; p < row_ptr[j + 1]; ++p)
                 z += (double)vals[p] * (double)Xin[(size_t)col_idx[p] * B + s];
             if (bias) z += (double)bias[j];
-            Xout[(size_t)j * B + s] = (REAL)act(z, cap);
+            Xout[(size_t)j * B + s] = (REAL)act(kind, z, cap);
         }
     }
 }
 
 /* Eq. 6 / Algorithm 1 line 5:  delta^L = grad_{x^L} J  (.)  f'(z^L). */
-void FN(oracle_output_delta)(int32_t n, int32_t B, const REAL *dLoss, const REAL *XL, double cap,
-                             REAL *DL)
+void FN(oracle_output_delta)(int32_t n, int32_t B, const REAL *dLoss, const REAL *XL, int kind,
+                             double cap, REAL *DL)
 {
     for (size_t e = 0; e < (size_t)n * B; ++e)
-        DL[e] = (REAL)((double)dLoss[e] * act_deriv_from_output((double)XL[e], cap));
+        DL[e] = (REAL)((double)dLoss[e] * act_deriv_from_output(kind, (double)XL[e], cap));
 }
 
 /* Eq. 7 / Algorithm 1 line 7:  Dprev = (W^T D) (.) f'(z_prev).
@@ -86,7 +93,7 @@ void FN(oracle_output_delta)(int32_t n, int32_t B, const REAL *dLoss, const REAL
  * If Xprev is NULL no derivative is applied (plain transposed product). */
 void FN(oracle_backward_layer)(int32_t n_out, int32_t n_in, const int32_t *row_ptr,
                                const int32_t *col_idx, const REAL *vals, const REAL *D,
-                               const REAL *Xprev, int32_t B, double cap, REAL *Dprev)
+                               const REAL *Xprev, int32_t B, int kind, double cap, REAL *Dprev)
 {
     double *S = (double *)calloc((size_t)n_in * B, sizeof(double));
 #pragma omp parallel for schedule(static)
@@ -98,7 +105,7 @@ void FN(oracle_backward_layer)(int32_t n_out, int32_t n_in, const int32_t *row_p
         }
     }
     for (size_t e = 0; e < (size_t)n_in * B; ++e) {
-        double m = Xprev ? act_deriv_from_output((double)Xprev[e], cap) : 1.0;
+        double m = Xprev ? act_deriv_from_output(kind, (double)Xprev[e], cap) : 1.0;
         Dprev[e] = (REAL)(S[e] * m);
     }
     free(S);

@@ -33,7 +33,7 @@ def build(force: bool = False) -> None:
         if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
             continue
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off",
-               f"-DREAL={real}", f"-DSUFFIX={suffix}", "-o", out, _SRC]
+               f"-DREAL={real}", f"-DSUFFIX={suffix}", "-o", out, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
 
 
@@ -51,7 +51,9 @@ def _ptr(a: Optional[np.ndarray]):
 class Oracle:
     """Oracle over one storage precision: np.float32 (default) or np.float64."""
 
-    def __init__(self, dtype=np.float32):
+    def __init__(self, dtype=np.float32, activation: str = "relu"):
+        """activation: "relu" (clamped at the cap passed to each call) or "sigmoid" (cap ignored)."""
+        self.kind = {"relu": 0, "sigmoid": 1}[activation]
         self.dtype = np.dtype(dtype)
         self.sfx = {"float32": "f32", "float64": "f64"}[self.dtype.name]
         self.lib = _lib(self.sfx)
@@ -80,7 +82,8 @@ class Oracle:
         bias = None if layer.bias is None else self._arr(layer.bias)
         self._fn("oracle_forward_layer")(
             ctypes.c_int32(layer.n_out), _ptr(layer.row_ptr), _ptr(layer.col_idx), _ptr(vals),
-            _ptr(bias), _ptr(x_in), ctypes.c_int32(b), ctypes.c_double(self._cap(cap)), _ptr(out))
+            _ptr(bias), _ptr(x_in), ctypes.c_int32(b), ctypes.c_int(self.kind), ctypes.c_double(self._cap(cap)),
+            _ptr(out))
         return out
 
     def output_delta(self, dloss: np.ndarray, x_last: np.ndarray, cap: float) -> np.ndarray:
@@ -90,7 +93,7 @@ class Oracle:
         out = np.empty_like(x_last)
         self._fn("oracle_output_delta")(
             ctypes.c_int32(x_last.shape[0]), ctypes.c_int32(x_last.shape[1]), _ptr(dloss),
-            _ptr(x_last), ctypes.c_double(self._cap(cap)), _ptr(out))
+            _ptr(x_last), ctypes.c_int(self.kind), ctypes.c_double(self._cap(cap)), _ptr(out))
         return out
 
     def backward_layer(self, layer, delta: np.ndarray, x_prev: Optional[np.ndarray],
@@ -106,7 +109,7 @@ class Oracle:
         self._fn("oracle_backward_layer")(
             ctypes.c_int32(layer.n_out), ctypes.c_int32(layer.n_in), _ptr(layer.row_ptr),
             _ptr(layer.col_idx), _ptr(vals), _ptr(delta), _ptr(x_prev), ctypes.c_int32(b),
-            ctypes.c_double(self._cap(cap)), _ptr(out))
+            ctypes.c_int(self.kind), ctypes.c_double(self._cap(cap)), _ptr(out))
         return out
 
     def weight_grad(self, layer, delta: np.ndarray, x_prev: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

@@ -292,3 +292,59 @@ def test_cap_is_a_number_of_the_storage_precision():
     assert (x1 == np.float32(0.9)).all()
     d = O32.output_delta(np.ones((4, 1), np.float32), x1, 0.9)
     assert (d == 0).all()
+
+
+# --------------------------------------------------------------------------
+# sigmoid activation (the paper's own training setup, Section 6.1)
+# --------------------------------------------------------------------------
+
+S64 = Oracle(np.float64, "sigmoid")
+S32 = Oracle(np.float32, "sigmoid")
+
+
+def test_sigmoid_forward_backward_match_dense_algebra():
+    net = wl.tiny_net(41, sizes=(9, 13, 11, 7), b=5)
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+    xs = [net.x_infer.astype(np.float64)]
+    for l in net.layers:
+        xs.append(sig(dense(l) @ xs[-1] + l.bias.astype(np.float64)[:, None]))
+    got = S64.forward(net.layers, net.x_infer, np.inf)
+    for k in range(1, 4):
+        np.testing.assert_allclose(got[k], xs[k], rtol=1e-13)
+        np.testing.assert_allclose(S32.forward(net.layers, net.x_infer, np.inf)[k], xs[k], rtol=3e-7)
+        assert (got[k] > 0).all() and (got[k] < 1).all()
+    dloss = np.random.default_rng(4).standard_normal(xs[-1].shape)
+    od = S64.backward(net.layers, got, dloss, np.inf)
+    d = [None] * 4
+    d[3] = dloss * xs[3] * (1 - xs[3])
+    for k in (3, 2):
+        d[k - 1] = (dense(net.layers[k - 1]).T @ d[k]) * xs[k - 1] * (1 - xs[k - 1])
+    for k in (1, 2, 3):
+        np.testing.assert_allclose(od[k], d[k], rtol=1e-12, atol=1e-15)
+    # closed form: zero weights and bias give 0.5 everywhere, f' = 0.25
+    lay = wl.regular_layer(5, 64, 32, 0.0, 0.0)
+    assert (S32.forward_layer(lay, np.ones((64, 2), np.float32), np.inf) == 0.5).all()
+    assert (S32.output_delta(np.ones((64, 2), np.float32), np.full((64, 2), 0.5, np.float32), np.inf) == 0.25).all()
+
+
+def test_sigmoid_gradients_by_finite_differences():
+    net = wl.tiny_net(42, sizes=(6, 8, 7, 5), b=3, density=0.5)
+    x0 = net.x_infer
+    xs = S64.forward(net.layers, x0, np.inf)
+    deltas = S64.backward(net.layers, xs, mse_dloss(xs[-1], net.targets), np.inf)
+    grads = S64.gradients(net.layers, xs, deltas)
+    for lay in net.layers:
+        lay.values = lay.values.astype(np.float64)
+        lay.bias = lay.bias.astype(np.float64)
+    J = lambda: mse_loss(S64.forward(net.layers, x0, np.inf)[-1], net.targets)
+    h, worst, scale = 1e-5, 0.0, max(np.abs(g).max() for g, _ in grads)
+    for k, lay in enumerate(net.layers):
+        for arr, g in ((lay.values, grads[k][0]), (lay.bias, grads[k][1])):
+            for p in range(arr.size):
+                keep = arr[p]
+                arr[p] = keep + h; jp = J()
+                arr[p] = keep - h; jm = J()
+                arr[p] = keep
+                worst = max(worst, abs((jp - jm) / (2 * h) - g[p]))
+                assert g[p] != 0
+    assert worst <= 1e-8 * max(scale, 1e-3), worst      # smooth activation: O(h^2) error only
