@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
     ap.add_argument("--layers", type=int, default=None, help="depth prefix (default: full depth)")
     ap.add_argument("--density", type=float, default=None, help="input density override (live inputs)")
+    ap.add_argument("--paper-setup", action="store_true",
+                    help="the paper's own training experiment: sigmoid, weights U[-1,1], one input vector per step")
+    ap.add_argument("--n", type=int, default=1024, help="neurons per layer for --paper-setup")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-inference", action="store_true")
     args = ap.parse_args()
@@ -53,6 +56,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.paper_setup:
+        return paper_setup_bench(args, np, torch, sdnn, wl)
     t0 = time.time()
     work = wl.make_config(args.config, n_layers=args.layers, density=args.density)
     N, L, nnz_total = work.n, len(work.layers), work.total_nnz
@@ -196,6 +201,64 @@ def main():
         "setup_s": {"generate": round(gen_s, 2)},
     }
     print(json.dumps(out))
+
+
+# Time per input vector of a full SGD step in the paper's strong-scaling figure (Section 6.3),
+# hypergraph-partitioned runs on 32 and on 512 cores of a Haswell/InfiniBand cluster, in ms.  Context only:
+# other hardware, the real benchmark nets, precision not stated.
+PAPER_MS_PER_VECTOR = {1024: (95.2, 41.1), 4096: (272.4, 81.6), 16384: (1143.1, 199.5), 65536: (6624.7, 571.2)}
+
+
+def paper_setup_bench(args, np, torch, sdnn, wl):
+    """One input vector per SGD step (B = 1), sigmoid, MSE, weights U[-1,1], lr 0.01, 120 layers."""
+    dev = "cuda:0"
+    L = args.layers or 120
+    work = wl.paper_training_setup(args.n, n_layers=L, n_inputs=64)
+    net = sdnn.Net(work.layers, work.act_cap, 1, training=True, activation="sigmoid")
+    xs = [torch.from_numpy(np.ascontiguousarray(work.x_infer[:, s:s + 1])).to(dev) for s in range(64)]
+    ys = [torch.from_numpy(np.ascontiguousarray(work.targets[:, s:s + 1])).to(dev) for s in range(64)]
+    xl = torch.empty(args.n, 1, device=dev)
+    dl = torch.empty_like(xl)
+
+    def step(i):
+        net.sdnn_forward(xs[i % 64], xl)
+        sdnn.sdnn_mse_dloss(xl, ys[i % 64], out=dl)
+        net.sdnn_backward(dl)
+        net.sdnn_sgd_step(work.lr)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.sdnn_oracle import Oracle, mse_dloss
+        orc = Oracle(np.float32, "sigmoid")
+        x0, y0 = work.x_infer[:, :1], work.targets[:, :1]
+        orc.train_step(work.layers, x0, work.act_cap, lambda x: mse_dloss(x, y0), work.lr)
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            orc.train_step(work.layers, x0, work.act_cap, lambda x: mse_dloss(x, y0), work.lr)
+        cs = (time.perf_counter() - t0) / reps
+        cpu = {"value": cs * 1e3, "unit": "ms per input vector", "cores": orc.threads(), "kind": "oracle",
+               "sample": f"{reps} full steps on one vector, all {L} layers"}
+    ctx = PAPER_MS_PER_VECTOR.get(args.n) if L == 120 else None
+    print(json.dumps({
+        "metric": "ms per input vector, full SGD step (forward+backward+update), one vector per step",
+        "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"paper training setup: N={args.n}, L={L}, 32 nnz/row, sigmoid, B=1",
+                   "total_nnz": work.total_nnz, "storage": "fp32", "accumulate": "fp64"},
+        "edges_per_s": work.total_nnz / (ms * 1e-3),
+        "paper_context_ms": None if ctx is None else {"32 cores": ctx[0], "512 cores": ctx[1],
+                                                      "note": "paper Fig. 4, other hardware and the real nets: context only"},
+        "cpu_baseline": cpu}))
+    net.close()
 
 
 if __name__ == "__main__":

@@ -8,7 +8,7 @@
  * product becomes W X):
  *
  *   forward   X_l = f(W_l X_{l-1} + b_l 1^T),  l = 1..L          (Eq. 3)
- *             f(z) = min(max(z, 0), act_cap)
+ *             f(z) = min(max(z, 0), act_cap)   or   1/(1+exp(-z))
  *   backward  Delta_L = dLoss (.) f'(Z_L)                        (Eq. 6)
  *             Delta_{l-1} = (W_l^T Delta_l) (.) f'(Z_{l-1})      (Eq. 7)
  *   update    W_l(j,i) -= lr * sum_s Delta_l(j,s) X_{l-1}(i,s)   (Eqs. 4-5)
@@ -16,8 +16,8 @@
  *             never changes.  b_l(j) -= lr * sum_s Delta_l(j,s) (the bias is
  *             the weight of a link from a constant-one neuron, Section 3.2).
  *
- * f'(z) is 1 for 0 < z < act_cap and 0 elsewhere; it is evaluated from the
- * stored output x = f(z).  Back-propagation uses the weights of the forward
+ * f'(z) is 1 for 0 < z < act_cap and 0 elsewhere (sigmoid: x(1-x)); it is
+ * evaluated from the stored output x = f(z).  Back-propagation uses the weights of the forward
  * pass (Algorithm 1 forms delta^{k-1} before it updates W^k); every update is
  * applied by sdnn_sgd_step.  Delta_0 is not formed.
  *
@@ -68,11 +68,15 @@ typedef struct {
     const float *bias;      /* [n_out] or NULL (= zeros)                       */
 } sdnn_layer;
 
+#define SDNN_ACT_RELU_CAP 0 /* f(z) = min(max(z,0),act_cap); f' = [0 < x < act_cap]                 */
+#define SDNN_ACT_SIGMOID 1  /* f(z) = 1/(1+exp(-z)); f' = x(1-x): the paper's training setup (Sec. 6.1) */
+
 typedef struct {
     float act_cap;       /* activation cap; +INFINITY = plain ReLU; must be > 0  */
     int32_t max_batch;   /* largest B a forward call may use (sizes the workspace) */
     int32_t training;    /* 1: keep X_0..X_L and Delta_1..Delta_L; 0: inference only */
     int32_t update_bias; /* 1: sdnn_sgd_step also updates the biases             */
+    int32_t activation;  /* SDNN_ACT_RELU_CAP or SDNN_ACT_SIGMOID (act_cap ignored) */
 } sdnn_config;
 
 /* ---- setup (Algorithm 1's inputs {W^k}; the paper likewise precomputes its

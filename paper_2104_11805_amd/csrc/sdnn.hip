@@ -82,6 +82,29 @@ __device__ __forceinline__ void gatherv(__amdgpu_buffer_rsrc_t r, unsigned lane_
     }
 }
 
+// Activations (the paper's Eq. 3 leaves f open; Section 6.1 trains with the sigmoid).
+//   ACT_RELU_CAP: f(z) = min(max(z, 0), cap), f' = [0 < x < cap] from the stored output x
+//   ACT_SIGMOID:  f(z) = 1 / (1 + exp(-z)),   f' = x (1 - x)     from the stored output x
+#define ACT_RELU_CAP 0
+#define ACT_SIGMOID 1
+__device__ __forceinline__ float act_apply(int act, double z, float capf)
+{
+    if (act == ACT_SIGMOID) return (float)(1.0 / (1.0 + exp(-z)));
+    const double cap = (double)capf;
+    z = z < 0.0 ? 0.0 : z;
+    z = z > cap ? cap : z;
+    return (float)z;
+}
+// value * f'(z) with f' taken from the stored output x
+__device__ __forceinline__ float act_backprop(int act, double value, float x, float capf)
+{
+    if (act == ACT_SIGMOID) {
+        const double xd = (double)x;
+        return (float)(value * (xd * (1.0 - xd)));
+    }
+    return (x > 0.0f && x < capf) ? (float)value : 0.0f;
+}
+
 // Workgroup ids are handed to the 8 XCDs round-robin and each XCD has its own
 // L2.  Give every XCD whole batch tiles (all row groups of tile x, x+8, ...)
 // so that the activation slab of a tile is gathered through one L2 only.  The
@@ -121,6 +144,7 @@ struct SpmmArgs {
     int32_t n_rows, B;
     uint32_t n_tiles, n_rg, n_vblocks;
     float cap;
+    int32_t act;
 };
 
 // The part of a row task that does not depend on the previous layer's output:
@@ -163,7 +187,7 @@ __device__ __forceinline__ RowMeta load_meta(const int32_t *order, const int32_t
 template <int V, int MODE, int U>
 __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const float *vals,
                                          const int32_t *perm, const float *in, size_t in_bytes,
-                                         float *out, const float *aux, int B, float capf,
+                                         float *out, const float *aux, int B, float capf, int act,
                                          unsigned tile, int lane)
 {
     const int s_own = (int)tile * (64 * V) + lane * V;
@@ -227,18 +251,12 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
     }
 
     float o[V];
-    const double cap = (double)capf;
     if (MODE == 0) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            double z = acc[v] + b;
-            z = z < 0.0 ? 0.0 : z;
-            z = z > cap ? cap : z;
-            o[v] = (float)z;
-        }
+        for (int v = 0; v < V; ++v) o[v] = act_apply(act, acc[v] + b, capf);
     } else {
 #pragma unroll
-        for (int v = 0; v < V; ++v) o[v] = (xp[v] > 0.0f && xp[v] < capf) ? (float)acc[v] : 0.0f;
+        for (int v = 0; v < V; ++v) o[v] = act_backprop(act, acc[v], xp[v], capf);
     }
     if (live) stv<V>(out + (size_t)m.row * ld + s, o);
 }
@@ -258,7 +276,7 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
         const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
         const RowMeta m = load_meta<MODE>(a.order, a.row_ptr, a.idx, a.vals, a.perm, r, lane);
-        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, tile, lane);
+        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile, lane);
     }
 }
 
@@ -267,12 +285,99 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_output_delta(const float *__restrict__ dloss,
                                                       const float *__restrict__ xl,
-                                                      float *__restrict__ d, size_t n, float cap)
+                                                      float *__restrict__ d, size_t n, float cap, int act)
 {
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
-         e += (size_t)gridDim.x * blockDim.x) {
-        const float x = xl[e];
-        d[e] = (x > 0.0f && x < cap) ? dloss[e] : 0.0f;
+         e += (size_t)gridDim.x * blockDim.x)
+        d[e] = act_backprop(act, (double)dloss[e], xl[e], cap);
+}
+
+// ---------------------------------------------------------------------------
+// One sample per step (B = 1, the paper's own training experiments: one input
+// vector per SGD step, Section 6.1).  Lanes over samples would idle 63 of 64
+// lanes, so here a lane owns a whole row and walks it in storage order (same
+// sum as everywhere else); the activation vector is a few KB and lives in L1/L2.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__global__ void __launch_bounds__(256) k_spmv(const SpmmArgs a)
+{
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= a.n_rows) return;
+    const int beg = a.row_ptr[row], end = a.row_ptr[row + 1];
+    double acc = 0.0;
+    constexpr int U = 16; // entries requested together; the additions stay in storage order
+    for (int p0 = beg; p0 < end; p0 += U) {
+        int c[U];
+        float w[U], x[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int p = min(p0 + k, end - 1);
+            c[k] = a.idx[p];
+            w[k] = MODE == 1 ? a.vals[a.perm[p]] : a.vals[p];
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) x[k] = a.in[c[k]];
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+            if (p0 + k < end) acc = fma((double)w[k], (double)x[k], acc);
+    }
+    if (MODE == 0) a.out[row] = act_apply(a.act, acc + (a.aux ? (double)a.aux[row] : 0.0), a.cap);
+    else a.out[row] = act_backprop(a.act, acc, a.aux[row], a.cap);
+}
+
+// Same product for narrow layers, where a lane per row leaves most of the chip idle: a wavefront
+// per row.  The row's entries and the activations they point at are fetched by two wave-wide loads
+// (entry k in lane k); the sum itself is still taken in storage order, every lane redoing it from
+// the broadcast operands.
+template <int MODE>
+__global__ void __launch_bounds__(BLOCK_THREADS) k_spmv_wave(const SpmmArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
+    if (row >= a.n_rows) return;
+    const int beg = a.row_ptr[row], end = a.row_ptr[row + 1];
+    double acc = 0.0;
+    for (int base = beg; base < end; base += 64) {
+        const int n = min(64, end - base);
+        float w_l = 0.0f, x_l = 0.0f;
+        if (lane < n) {
+            const int p = base + lane;
+            w_l = MODE == 1 ? a.vals[a.perm[p]] : a.vals[p];
+            x_l = a.in[a.idx[p]];
+        }
+        for (int k = 0; k < n; ++k) {
+            const double wk = (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_l), k));
+            const double xk = (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(x_l), k));
+            acc = fma(wk, xk, acc);
+        }
+    }
+    if (lane == 0) {
+        if (MODE == 0) a.out[row] = act_apply(a.act, acc + (a.aux ? (double)a.aux[row] : 0.0), a.cap);
+        else a.out[row] = act_backprop(a.act, acc, a.aux[row], a.cap);
+    }
+}
+
+// Update for B = 1: no sum over samples, so the lanes of a wavefront take the
+// entries of its row: vals[p] -= lr * delta(row) * x(col[p]); lane 0 does the bias.
+__global__ void __launch_bounds__(BLOCK_THREADS)
+k_update_b1(const LayerDev *__restrict__ layers, int layer0, float lr, int update_bias, int emit,
+            float *__restrict__ g_out, float *__restrict__ gb_out)
+{
+    const LayerDev &L = layers[layer0 + blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= L.n_out) return;
+    const int beg = L.row_ptr[row], end = L.row_ptr[row + 1];
+    const float d = L.D[row];
+    const double dlr = (double)lr;
+    for (int p = beg + lane; p < end; p += 64) {
+        const float g = (float)((double)d * (double)L.X_prev[L.col_idx[p]]);
+        if (emit) { if (g_out) g_out[p] = g; }
+        else L.vals[p] = (float)((double)L.vals[p] - dlr * (double)g);
+    }
+    if (lane == 0) {
+        if (emit) { if (gb_out) gb_out[row] = d; }
+        else if (update_bias) L.bias[row] = (float)((double)L.bias[row] - dlr * (double)d);
     }
 }
 
@@ -493,7 +598,10 @@ static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_c
     if (!layers || !cfg) return fail(nullptr, SDNN_EINVAL, "layers or cfg is NULL");
     if (n_layers < 1) return fail(nullptr, SDNN_EINVAL, "n_layers must be >= 1");
     if (cfg->max_batch < 1) return fail(nullptr, SDNN_EINVAL, "max_batch must be >= 1");
-    if (!(cfg->act_cap > 0.0f)) return fail(nullptr, SDNN_EINVAL, "act_cap must be > 0 (or +inf)");
+    if (cfg->activation != SDNN_ACT_RELU_CAP && cfg->activation != SDNN_ACT_SIGMOID)
+        return fail(nullptr, SDNN_EINVAL, "unknown activation %d", cfg->activation);
+    if (cfg->activation == SDNN_ACT_RELU_CAP && !(cfg->act_cap > 0.0f))
+        return fail(nullptr, SDNN_EINVAL, "act_cap must be > 0 (or +inf)");
     for (int32_t l = 0; l < n_layers; ++l) {
         const sdnn_layer &y = layers[l];
         if (y.n_out < 0 || y.n_in < 0 || !y.row_ptr)
@@ -690,11 +798,20 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
         a.row_ptr = d.t_row_ptr; a.idx = d.t_row_idx; a.perm = d.t_perm; a.order = d.t_order;
         a.n_rows = d.n_in;
     }
-    a.vals = d.vals; a.in = in; a.out = out; a.aux = aux; a.B = B; a.cap = net->cfg.act_cap;
+    a.vals = d.vals; a.in = in; a.out = out; a.aux = aux; a.B = B; a.cap = net->cfg.act_cap; a.act = net->cfg.activation;
     if (a.n_rows == 0) return SDNN_OK;
     a.in_bytes = 4 * (size_t)(MODE == 0 ? d.n_in : d.n_out) * (size_t)B;
     if (a.in_bytes >= ((size_t)1 << 32))
         return fail(net, SDNN_EINVAL, "activation block of %zu bytes exceeds 4 GiB: use a smaller B", a.in_bytes);
+    if (B == 1) {
+        if (a.n_rows <= 16384) // a wavefront per row while that still fits the chip a few times over (measured crossover)
+            hipLaunchKernelGGL(k_spmv_wave<MODE>, dim3((unsigned)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK)),
+                               dim3(BLOCK_THREADS), 0, stream, a);
+        else
+            hipLaunchKernelGGL(k_spmv<MODE>, dim3((unsigned)((a.n_rows + 255) / 256)), dim3(256), 0, stream, a);
+        HIP_TRY(net, hipGetLastError());
+        return SDNN_OK;
+    }
     const int V = pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
     a.n_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
@@ -769,7 +886,7 @@ extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
     const size_t n = (size_t)last.n_out * B;
     if (n) {
         hipLaunchKernelGGL(k_output_delta, dim3(ew_blocks(n)), dim3(256), 0, stream, d_dLoss, last.X,
-                           last.D, n, net->cfg.act_cap);
+                           last.D, n, net->cfg.act_cap, net->cfg.activation);
         HIP_TRY(net, hipGetLastError());
     }
     for (int l = L - 1; l >= 1; --l) {
@@ -794,6 +911,16 @@ static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int 
     for (int l = layer0; l < layer0 + n_layers; ++l) max_rows = std::max(max_rows, net->layers[l].n_out);
     if (max_rows == 0) return SDNN_OK;
     const int B = net->B;
+    if (B == 1) {
+        for (int l0 = 0; l0 < n_layers; l0 += 65535) {
+            const int nl = std::min(65535, n_layers - l0);
+            dim3 grid((unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), (unsigned)nl);
+            hipLaunchKernelGGL(k_update_b1, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers, layer0 + l0, lr,
+                               net->cfg.update_bias, emit, g, gb);
+            HIP_TRY(net, hipGetLastError());
+        }
+        return SDNN_OK;
+    }
     // all activation / delta buffers are 256-byte aligned; rows are aligned iff B % 4 == 0
     const int V = pick_v_update(B, net->layers[layer0].D, net->layers[layer0].X_prev);
     // grid.x enumerates (group of 8 layers, row group, layer inside the group)

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsdnn.so")
 
 SDNN_OK, SDNN_EINVAL, SDNN_ESTATE, SDNN_ENOMEM, SDNN_EHIP = 0, -1, -2, -3, -4
+SDNN_ACT_RELU_CAP, SDNN_ACT_SIGMOID = 0, 1
 
 
 class SdnnError(RuntimeError):
@@ -32,7 +33,7 @@ class sdnn_layer(C.Structure):
 
 class sdnn_config(C.Structure):
     _fields_ = [("act_cap", C.c_float), ("max_batch", C.c_int32), ("training", C.c_int32),
-                ("update_bias", C.c_int32)]
+                ("update_bias", C.c_int32), ("activation", C.c_int32)]
 
 
 # name -> (restype, argtypes); every symbol include/sdnn.h declares
@@ -137,7 +138,7 @@ class Net:
     """Owns the workspace tensor and the opaque sdnn_net handle."""
 
     def __init__(self, layers: Sequence, act_cap: float, max_batch: int, training: bool = True,
-                 update_bias: bool = True, device: str = "cuda:0"):
+                 update_bias: bool = True, device: str = "cuda:0", activation: str = "relu"):
         import torch
         self._handle = None
         self._keep = []
@@ -149,7 +150,8 @@ class Net:
             arr[k] = sdnn_layer(l.n_out, l.n_in, _hp(rp).value, _hp(ci).value,
                                 _hp(va).value if va.size else None,
                                 None if bi is None else _hp(bi).value)
-        self.cfg = sdnn_config(float(act_cap), int(max_batch), int(training), int(update_bias))
+        self.cfg = sdnn_config(float(act_cap), int(max_batch), int(training), int(update_bias),
+                               {"relu": SDNN_ACT_RELU_CAP, "sigmoid": SDNN_ACT_SIGMOID}[activation])
         nbytes = C.c_size_t(0)
         _check(lib().sdnn_workspace_bytes(arr, len(layers), C.byref(self.cfg), C.byref(nbytes)))
         self.device = torch.device(device)

@@ -52,6 +52,7 @@ class Workload:
     targets: Optional[np.ndarray] = None   # float32 [N][train_batch]  (mse)
     labels: Optional[np.ndarray] = None    # int64 [train_batch]       (softmax_ce)
     n_classes: int = 0
+    activation: str = "relu"               # "relu" (clamped at act_cap) | "sigmoid"
     meta: dict = field(default_factory=dict)
 
     @property
@@ -234,6 +235,27 @@ def make_config(cfg: int, *, n_layers: Optional[int] = None, n: Optional[int] = 
         return Workload(f"cfg5-N{N}-L{L}", layers, float("inf"), x, Bt, "softmax_ce", 0.005,
                         labels=lab, n_classes=10, meta=dict(cfg=5))
     raise ValueError("cfg must be 1..5")
+
+
+def paper_training_setup(n: int, n_layers: int = 120, n_inputs: int = 64, seed: int = 7000,
+                         input_density: float = 0.19) -> Workload:
+    """The paper's own training experiment (Section 6.1) on a synthetic stand-in net:
+    sigmoid activation, MSE loss, weights uniform in [-1, 1], learning rate 0.01, ONE input
+    vector per SGD step.  Topology as in configs 1-4 (32 links per neuron at distinct uniform
+    sources: the benchmark nets themselves are not available offline); biases start at 0 and are
+    trained (the paper folds the bias into W).  Inputs: `n_inputs` binary vectors (stand-ins for
+    thresholded images; about 19 % of MNIST pixels are on), targets uniform in [0, 1).
+    Use column s of x_infer / targets for step s."""
+    layers = []
+    for l in range(1, n_layers + 1):
+        lay = regular_layer(seed + l, n, 32, 0.0, 0.0)
+        rng = np.random.default_rng(seed + 500 + l)
+        lay.values = rng.uniform(-1.0, 1.0, size=lay.nnz).astype(np.float32)
+        layers.append(lay)
+    x = binary_inputs(seed + 900, n, n_inputs, input_density)
+    tg = uniform_targets(seed + 901, n, n_inputs)
+    return Workload(f"paper-setup-N{n}-L{n_layers}", layers, float("inf"), x, 1, "mse", 0.01, targets=tg,
+                    activation="sigmoid", meta=dict(setup="paper section 6.1"))
 
 
 def tiny_net(seed: int, sizes=(7, 9, 6, 8), density: float = 0.45, b: int = 5,

@@ -177,3 +177,42 @@ def test_loss_gradient_kernels():
     assert (got[:30] == 0).all()
     np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-9)
     assert abs(got[30:].sum()) < 1e-6
+
+
+@pytest.mark.parametrize("b", [1, 3, 64, 128])
+def test_sigmoid_training_step(b):
+    """The paper's own activation (Section 6.1), small rectangular net, several batch sizes
+    including one vector per step (B = 1 takes the lane-per-row kernels)."""
+    work = wl.tiny_net(51, sizes=(40, 70, 33, 50), density=0.3, b=b)
+    work.activation = "sigmoid"
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05)
+    st = P.compare_step(g, o, f"sigmoid b={b}", exact_fwd=False)
+    assert st["live_g"] == 3 and st["live_d"] == 3
+    assert st["bitexact_x"] >= 3          # exp() may differ in the last bit of a double, rarely visible in fp32
+
+
+def test_paper_training_setup_one_vector_per_step():
+    """Sigmoid, weights U[-1,1], lr 0.01, B = 1 on a 1024-wide, 12-layer stand-in net: three
+    consecutive SGD steps on three input vectors, weights carried over, against the oracle."""
+    work = wl.paper_training_setup(1024, n_layers=12, n_inputs=4)
+    orc = P.ORACLES["sigmoid"]
+    net = sdnn.Net(work.layers, work.act_cap, 1, training=True, activation="sigmoid")
+    layers = work.layers
+    for s in range(3):
+        x0 = np.ascontiguousarray(work.x_infer[:, s:s + 1])
+        y = np.ascontiguousarray(work.targets[:, s:s + 1])
+        xl = torch.empty(1024, 1, device=P.DEV)
+        net.sdnn_forward(P.dev(x0), xl)
+        net.sdnn_backward(sdnn.sdnn_mse_dloss(xl, P.dev(y)))
+        net.sdnn_sgd_step(work.lr)
+        xs, deltas, grads, new = orc.train_step(layers, x0, work.act_cap, lambda x: P.mse_dloss(x, y), work.lr)
+        P.assert_forward_close(P.host(xl), xs[-1], f"step {s} X_L")
+        for k, (lay, (v, b)) in enumerate(zip(layers, new)):
+            gv, gb = (P.host(t) for t in net.sdnn_get_weights(k + 1))
+            P.assert_grad_close(gv, v, f"step {s} layer {k + 1} weights")
+            P.assert_grad_close(gb, b, f"step {s} layer {k + 1} bias")
+            assert (v != lay.values).any()
+            # carry the ORACLE's weights forward on the oracle side, the GPU keeps its own
+            lay.values, lay.bias = v, b
+    net.close()

@@ -102,21 +102,26 @@ def test_workspace_bytes_and_argument_errors_without_gpu():
     arr, keep = _layer_array(net.layers)
     l = sdnn.lib()
     n = C.c_size_t(0)
-    cfg = sdnn.sdnn_config(float("inf"), 16, 1, 1)
+    cfg = sdnn.sdnn_config(float("inf"), 16, 1, 1, 0)
     assert l.sdnn_workspace_bytes(arr, 3, C.byref(cfg), C.byref(n)) == 0
     train_bytes = n.value
     nnz = sum(x.nnz for x in net.layers)
     # CSR + transposed index (5 x 4 bytes per entry) + activations and deltas
     assert train_bytes >= 20 * nnz + 4 * 16 * (2 * (9 + 6 + 8) + 7)
-    cfg_inf = sdnn.sdnn_config(float("inf"), 16, 0, 1)
+    cfg_inf = sdnn.sdnn_config(float("inf"), 16, 0, 1, 0)
     assert l.sdnn_workspace_bytes(arr, 3, C.byref(cfg_inf), C.byref(n)) == 0
     assert 0 < n.value < train_bytes
     # argument errors are reported before any GPU work
-    bad = sdnn.sdnn_config(float("inf"), 0, 1, 1)
+    bad = sdnn.sdnn_config(float("inf"), 0, 1, 1, 0)
     assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
-    bad = sdnn.sdnn_config(0.0, 4, 1, 1)
+    bad = sdnn.sdnn_config(0.0, 4, 1, 1, 0)
     assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
     assert l.sdnn_workspace_bytes(arr, 0, C.byref(cfg), C.byref(n)) == sdnn.SDNN_EINVAL
+    bad = sdnn.sdnn_config(32.0, 4, 1, 1, 7)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
+    assert "activation" in sdnn.last_error()
+    sig = sdnn.sdnn_config(0.0, 4, 1, 1, sdnn.SDNN_ACT_SIGMOID)      # the cap is ignored for the sigmoid
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(sig), C.byref(n)) == 0
     h = C.c_void_p(1)
     assert l.sdnn_create(arr, 3, C.byref(cfg), None, train_bytes, None, C.byref(h)) == sdnn.SDNN_EINVAL
     assert h.value is None
@@ -138,7 +143,7 @@ def test_malformed_layer_is_rejected_by_create_without_gpu():
     net.layers[1].col_idx = net.layers[1].col_idx.copy()
     net.layers[1].col_idx[0] = 99
     arr, keep = _layer_array(net.layers)
-    cfg = sdnn.sdnn_config(32.0, 4, 1, 1)
+    cfg = sdnn.sdnn_config(32.0, 4, 1, 1, 0)
     h = C.c_void_p()
     assert sdnn.lib().sdnn_create(arr, 2, C.byref(cfg), C.c_void_p(4096), 1 << 30, None, C.byref(h)) == sdnn.SDNN_EINVAL
     assert "layer 2" in sdnn.last_error()
