@@ -136,7 +136,7 @@ struct SpmmArgs {
     const int32_t *idx;
     const float *vals;
     const int32_t *perm;  // MODE 1 only
-    const int32_t *order; // rows by decreasing length
+    const int4 *sched;    // per task: {row, first entry, end of entries, 0}, rows by decreasing length
     const float *in;      // [n_cols][B]
     size_t in_bytes;      // < 4 GiB
     float *out;           // [n_rows][B]
@@ -169,14 +169,14 @@ __device__ __forceinline__ void load_chunk(const int32_t *idx, const float *vals
 }
 
 template <int MODE>
-__device__ __forceinline__ RowMeta load_meta(const int32_t *order, const int32_t *row_ptr,
-                                             const int32_t *idx, const float *vals,
+__device__ __forceinline__ RowMeta load_meta(const int4 *sched, const int32_t *idx, const float *vals,
                                              const int32_t *perm, int r, int lane)
 {
     RowMeta m;
-    m.row = order[r];
-    m.beg = row_ptr[m.row];
-    m.end = row_ptr[m.row + 1];
+    const int4 t = sched[r]; // one (scalar) load instead of the chain order -> row_ptr
+    m.row = t.x;
+    m.beg = t.y;
+    m.end = t.z;
     load_chunk<MODE>(idx, vals, perm, m.beg, m.end, lane, m.c_l, m.w_l);
     return m;
 }
@@ -275,7 +275,7 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
         map_block(vb, a.n_tiles, a.n_rg, tile, rg);
         const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
-        const RowMeta m = load_meta<MODE>(a.order, a.row_ptr, a.idx, a.vals, a.perm, r, lane);
+        const RowMeta m = load_meta<MODE>(a.sched, a.idx, a.vals, a.perm, r, lane);
         spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile, lane);
     }
 }
@@ -406,8 +406,8 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, unsigned
     const int lane = threadIdx.x & 63;
     const int r = __builtin_amdgcn_readfirstlane((int)((within >> 3) * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
     if (r >= L.n_out) return;
-    const int row = L.order[r];
-    const int beg = L.row_ptr[row], end = L.row_ptr[row + 1];
+    const int4 task = L.sched[r];
+    const int row = task.x, beg = task.y, end = task.z;
     const unsigned ldb = 4u * (unsigned)B;
     const double dlr = (double)lr;
     const bool want_bias = emit ? gb_out != nullptr : update_bias != 0;
@@ -587,7 +587,7 @@ static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 // Workspace plan: offsets of every array, in one pass (also used to size it).
 struct Plan {
     struct PerLayer {
-        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, order, t_order, X, D;
+        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D;
     };
     std::vector<PerLayer> pl;
     size_t table = 0, x0 = 0, ping = 0, pong = 0, total = 0;
@@ -634,8 +634,8 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
         q.t_row_ptr = take(4 * ((size_t)y.n_in + 1));
         q.t_row_idx = take(4 * nnz);
         q.t_perm = take(4 * nnz);
-        q.order = take(4 * (size_t)y.n_out);
-        q.t_order = take(4 * (size_t)y.n_in);
+        q.sched = take(16 * (size_t)y.n_out);
+        q.t_sched = take(16 * (size_t)y.n_in);
         q.X = q.D = 0;
         if (cfg->training) {
             q.X = take(4 * (size_t)y.n_out * mb);
@@ -699,6 +699,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     auto fail_free = [&](int code) { delete net; return code; };
 
     std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
+    std::vector<int4> sched, t_sched;
     std::vector<float> zeros;
     for (int32_t l = 0; l < n_layers; ++l) {
         const sdnn_layer &y = layers[l];
@@ -713,6 +714,12 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                                t_row_idx.data(), t_perm.data());
         sdnn_row_schedule(y.n_out, y.row_ptr, order.data());
         sdnn_row_schedule(y.n_in, t_row_ptr.data(), t_order.data());
+        sched.resize(y.n_out);
+        t_sched.resize(y.n_in);
+        for (int32_t r = 0; r < y.n_out; ++r)
+            sched[r] = make_int4(order[r], y.row_ptr[order[r]], y.row_ptr[order[r] + 1], 0);
+        for (int32_t r = 0; r < y.n_in; ++r)
+            t_sched[r] = make_int4(t_order[r], t_row_ptr[t_order[r]], t_row_ptr[t_order[r] + 1], 0);
 
         LayerDev &d = net->layers[l];
         d.n_out = y.n_out; d.n_in = y.n_in; d.nnz = (int32_t)nnz; d.pad_ = 0;
@@ -723,8 +730,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         d.t_row_ptr = (const int32_t *)(base + q.t_row_ptr);
         d.t_row_idx = (const int32_t *)(base + q.t_row_idx);
         d.t_perm = (const int32_t *)(base + q.t_perm);
-        d.order = (const int32_t *)(base + q.order);
-        d.t_order = (const int32_t *)(base + q.t_order);
+        d.sched = (const int4 *)(base + q.sched);
+        d.t_sched = (const int4 *)(base + q.t_sched);
         d.X = cfg->training ? (float *)(base + q.X) : nullptr;
         d.D = cfg->training ? (float *)(base + q.D) : nullptr;
         d.X_prev = !cfg->training ? nullptr
@@ -750,8 +757,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         UP(d.t_row_ptr, t_row_ptr.data(), 4 * ((size_t)y.n_in + 1));
         UP(d.t_row_idx, t_row_idx.data(), 4 * nnz);
         UP(d.t_perm, t_perm.data(), 4 * nnz);
-        UP(d.order, order.data(), 4 * (size_t)y.n_out);
-        UP(d.t_order, t_order.data(), 4 * (size_t)y.n_in);
+        UP(d.sched, sched.data(), 16 * (size_t)y.n_out);
+        UP(d.t_sched, t_sched.data(), 16 * (size_t)y.n_in);
     }
     net->d_layers = (LayerDev *)(base + pl.table);
     UP(net->d_layers, net->layers.data(), sizeof(LayerDev) * (size_t)n_layers);
@@ -792,10 +799,10 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
 {
     SpmmArgs a;
     if (MODE == 0) {
-        a.row_ptr = d.row_ptr; a.idx = d.col_idx; a.perm = nullptr; a.order = d.order;
+        a.row_ptr = d.row_ptr; a.idx = d.col_idx; a.perm = nullptr; a.sched = d.sched;
         a.n_rows = d.n_out;
     } else {
-        a.row_ptr = d.t_row_ptr; a.idx = d.t_row_idx; a.perm = d.t_perm; a.order = d.t_order;
+        a.row_ptr = d.t_row_ptr; a.idx = d.t_row_idx; a.perm = d.t_perm; a.sched = d.t_sched;
         a.n_rows = d.n_in;
     }
     a.vals = d.vals; a.in = in; a.out = out; a.aux = aux; a.B = B; a.cap = net->cfg.act_cap; a.act = net->cfg.activation;

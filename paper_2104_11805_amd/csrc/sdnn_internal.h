@@ -5,6 +5,8 @@
 
 #include "../../include/sdnn.h"
 
+#include <hip/hip_vector_types.h> // int4
+
 void sdnn_set_global_error(const char *fmt, ...);
 const char *sdnn_global_error();
 
@@ -18,8 +20,8 @@ struct LayerDev {
     const int32_t *t_row_ptr; // [n_in+1]   transposed index (rows of W^T = columns of W)
     const int32_t *t_row_idx; // [nnz]
     const int32_t *t_perm;    // [nnz]      position of the entry in vals
-    const int32_t *order;     // [n_out]    rows of W by decreasing length
-    const int32_t *t_order;   // [n_in]     rows of W^T by decreasing length
+    const int4 *sched;        // [n_out]    {row, first entry, end, 0}, rows of W by decreasing length
+    const int4 *t_sched;      // [n_in]     the same for the rows of W^T
     float *X_prev;            // X_{l-1}  [n_in][B]   (training mode)
     float *X;                 // X_l      [n_out][B]  (training mode)
     float *D;                 // Delta_l  [n_out][B]  (training mode)
