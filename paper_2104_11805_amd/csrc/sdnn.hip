@@ -392,84 +392,72 @@ k_update_b1(const LayerDev *__restrict__ layers, int layer0, float lr, int updat
 // ---------------------------------------------------------------------------
 template <int V>
 __global__ void __launch_bounds__(BLOCK_THREADS)
-k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, unsigned n_rg, int B, float lr,
-         int update_bias,
-         int emit, float *__restrict__ g_out, float *__restrict__ gb_out)
+k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int interleave, int B, float lr,
+         int update_bias, int emit, float *__restrict__ g_out, float *__restrict__ gb_out)
 {
-    // Workgroup ids are dealt to the 8 XCDs round-robin.  Eight consecutive layers are interleaved
-    // so that XCD x works on layer 8q + x: all gathers of one layer go through one L2, which then
-    // fetches that layer's activations once instead of once per XCD.
-    const unsigned lgroup = blockIdx.x / (8u * n_rg), within = blockIdx.x % (8u * n_rg);
-    const int layer_rel = (int)(8u * lgroup + (within & 7u));
+    // interleaved: grid = (8 * row groups, groups of 8 layers), blockIdx.x % 8 is both the XCD and the
+    // layer inside the group, so all gathers of one layer go through one L2, which then fetches that
+    // layer's activations once instead of once per XCD.  Plain (few layers: the XCDs would not all
+    // have one): grid = (row groups, layers).
+    const int layer_rel = interleave ? (int)(8u * blockIdx.y + (blockIdx.x & 7u)) : (int)blockIdx.y;
     if (layer_rel >= n_layers) return;
     const LayerDev &L = layers[layer0 + layer_rel];
     const int lane = threadIdx.x & 63;
-    const int r = __builtin_amdgcn_readfirstlane((int)((within >> 3) * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
+    const unsigned rgi = interleave ? (blockIdx.x >> 3) : blockIdx.x;
+    const int r = __builtin_amdgcn_readfirstlane((int)(rgi * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
     if (r >= L.n_out) return;
     const int4 task = L.sched[r];
     const int row = task.x, beg = task.y, end = task.z;
-    const unsigned ldb = 4u * (unsigned)B;
+    const size_t ld = (size_t)B;
+    const float *drow = L.D + (size_t)row * ld;
+    const float *xp = L.X_prev;
     const double dlr = (double)lr;
-    const bool want_bias = emit ? gb_out != nullptr : update_bias != 0;
-    const bool want_g = !(emit && g_out == nullptr);
-    const int sg = lane & 15, eg = lane >> 4;
-    const unsigned so = 4u * (unsigned)(sg * V); // byte offset of this lane's first sample
-    // descriptors: the Delta row of this matrix row, and the whole X_{l-1} block (reads past the end give 0)
-    const __amdgpu_buffer_rsrc_t rd = make_rsrc(L.D + (size_t)row * B, ldb);
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(L.X_prev, (size_t)L.n_in * ldb);
-    const int n_pass = (B + 16 * V - 1) / (16 * V);
 
-    double bsum = 0.0;
-    bool first_chunk = true;
-    for (int base = beg; base < end || (first_chunk && want_bias); base += 32) {
+    // bias gradient: sum of the row of Delta over the samples
+    if (emit ? gb_out != nullptr : update_bias != 0) {
+        double sum = 0.0;
+        for (int s = lane * V; s < B; s += 64 * V) {
+            float d[V];
+            ldv<V>(drow + s, d);
+#pragma unroll
+            for (int v = 0; v < V; ++v) sum += (double)d[v];
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+        if (lane == 0) {
+            const float gb = (float)sum;
+            if (emit) gb_out[row] = gb;
+            else L.bias[row] = (float)((double)L.bias[row] - dlr * (double)gb);
+        }
+    }
+    if (emit && g_out == nullptr) return;
+
+    const int sg = lane & 15, eg = lane >> 4;
+    for (int base = beg; base < end; base += 32) {
         const int p0 = base + eg * 8;
-        unsigned coff[8];
+        size_t coff[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int p = p0 + k;
-            // slots past the end of the row re-read the row's first entry; their sums are dropped
-            coff[k] = (p < end ? (unsigned)L.col_idx[p] : (beg < end ? (unsigned)L.col_idx[beg] : 0u)) * ldb + so;
+            coff[k] = (size_t)(p < end ? L.col_idx[p] : L.col_idx[beg]) * ld;
         }
         double a[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = 0.0;
-        if (want_g || first_chunk) {
-            for (int t = 0; t < n_pass; ++t) {
-                const unsigned po = (unsigned)t * (64u * V); // byte offset of pass t inside a row (scalar)
-                float df[V];
-                gatherv<V>(rd, so + po, 0u, df); // lanes past the end of the batch read 0 (range-checked offset)
-                float x[8][V];
-                if (want_g && base < end) {
+        for (int s = sg * V; s < B; s += 16 * V) {
+            float df[V];
+            ldv<V>(drow + s, df);
+            float x[8][V];
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) gatherv<V>(rx, coff[k], po, x[k]);
-                }
-                double d[V];
+            for (int k = 0; k < 8; ++k) ldv<V>(xp + coff[k] + s, x[k]);
+            double d[V];
 #pragma unroll
-                for (int v = 0; v < V; ++v) d[v] = (double)df[v];
-                if (first_chunk) {
+            for (int v = 0; v < V; ++v) d[v] = (double)df[v];
 #pragma unroll
-                    for (int v = 0; v < V; ++v) bsum += d[v];
-                }
-                if (want_g && base < end) {
+            for (int k = 0; k < 8; ++k)
 #pragma unroll
-                    for (int k = 0; k < 8; ++k)
-#pragma unroll
-                        for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
-                }
-            }
+                for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
         }
-        if (first_chunk && want_bias) {
-            // bias gradient: sum of the Delta row over the samples (the 16 sample lanes of edge group 0)
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) bsum += __shfl_xor(bsum, off);
-            if (lane == 0) {
-                const float gb = (float)bsum;
-                if (emit) gb_out[row] = gb;
-                else L.bias[row] = (float)((double)L.bias[row] - dlr * (double)gb);
-            }
-        }
-        first_chunk = false;
-        if (!want_g || base >= end) break;
         // 16-lane transpose-reduce: 8 values/lane -> 1 value/lane (register indices are compile-time)
         {
             const bool up8 = (lane & 8) != 0, up4 = (lane & 4) != 0, up2 = (lane & 2) != 0;
@@ -825,15 +813,27 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     const uint64_t blocks = (uint64_t)a.n_tiles * a.n_rg;
     if (blocks > 0x7fffffffull) return fail(net, SDNN_EINVAL, "grid too large");
     a.n_vblocks = (uint32_t)blocks;
-    // 8 gathers in flight per lane measured best (16 costs a third of the occupancy, 4 exposes latency)
-    const void *fn = V == 4 ? (const void *)k_spmm<4, MODE, 8> : V == 2 ? (const void *)k_spmm<2, MODE, 8>
-                                                                      : (const void *)k_spmm<1, MODE, 8>;
-    int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0];
-    if (per_cu == 0) {
-        HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BLOCK_THREADS, 0));
-        if (per_cu < 1) per_cu = 1;
+    // Measured policy.  Short rows (a few tens of entries): 8 gathers in flight per lane (16 costs a
+    // third of the occupancy) and a grid of what the chip holds at once, whose workgroups walk the
+    // virtual blocks.  Long, uneven rows (hundreds of entries): 16 in flight and one workgroup per
+    // virtual block, so that the hardware hands out the rows, longest first, as wavefronts retire.
+    const bool long_rows = (int64_t)d.nnz >= 128 * (int64_t)a.n_rows;
+    const void *fn;
+    if (long_rows)
+        fn = V == 4 ? (const void *)k_spmm<4, MODE, 16> : V == 2 ? (const void *)k_spmm<2, MODE, 16>
+                                                                 : (const void *)k_spmm<1, MODE, 16>;
+    else
+        fn = V == 4 ? (const void *)k_spmm<4, MODE, 8> : V == 2 ? (const void *)k_spmm<2, MODE, 8>
+                                                                : (const void *)k_spmm<1, MODE, 8>;
+    uint64_t g = blocks;
+    if (!long_rows) {
+        int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0];
+        if (per_cu == 0) {
+            HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BLOCK_THREADS, 0));
+            if (per_cu < 1) per_cu = 1;
+        }
+        g = std::min(blocks, (uint64_t)per_cu * (uint64_t)net->n_cu);
     }
-    uint64_t g = std::min(blocks, (uint64_t)per_cu * (uint64_t)net->n_cu);
     if (g >= 8) g &= ~(uint64_t)7; // keeps virtual block id % 8 == workgroup id % 8 (XCD-wise tiles)
     void *args[] = {(void *)&a};
     HIP_TRY(net, hipLaunchKernel(fn, dim3((unsigned)g), dim3(BLOCK_THREADS), args, 0, stream));
@@ -930,19 +930,18 @@ static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int 
     }
     // all activation / delta buffers are 256-byte aligned; rows are aligned iff B % 4 == 0
     const int V = pick_v_update(B, net->layers[layer0].D, net->layers[layer0].X_prev);
-    // grid.x enumerates (group of 8 layers, row group, layer inside the group)
-    const uint64_t n_rg = (uint64_t)(max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    const uint64_t per_group = 8 * n_rg;
-    const int groups_per_launch = (int)std::max<uint64_t>(1, std::min<uint64_t>(0x7fffffffull / per_group, 1u << 20));
-    for (int l0 = 0; l0 < n_layers; l0 += 8 * groups_per_launch) {
-        const int nl = std::min(8 * groups_per_launch, n_layers - l0);
-        dim3 grid((unsigned)(per_group * (uint64_t)((nl + 7) / 8)));
+    const unsigned n_rg = (unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    // with many layers, interleave them over the XCDs (one L2 per layer); with few, keep all XCDs on each layer
+    const int interleave = n_layers >= 64;
+    for (int l0 = 0; l0 < n_layers; l0 += 65535) {
+        const int nl = std::min(65535, n_layers - l0);
+        dim3 grid(interleave ? 8u * n_rg : n_rg, (unsigned)(interleave ? (nl + 7) / 8 : nl));
         if (V == 4)
             hipLaunchKernelGGL(k_update<4>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
-                               layer0 + l0, nl, (unsigned)n_rg, B, lr, net->cfg.update_bias, emit, g, gb);
+                               layer0 + l0, nl, interleave, B, lr, net->cfg.update_bias, emit, g, gb);
         else
             hipLaunchKernelGGL(k_update<1>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
-                               layer0 + l0, nl, (unsigned)n_rg, B, lr, net->cfg.update_bias, emit, g, gb);
+                               layer0 + l0, nl, interleave, B, lr, net->cfg.update_bias, emit, g, gb);
         HIP_TRY(net, hipGetLastError());
     }
     return SDNN_OK;
