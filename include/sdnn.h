@@ -33,8 +33,11 @@
  *
  * Pointers named d_* are DEVICE pointers, all others are HOST pointers.
  * `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
- * device work is enqueued on that stream and is asynchronous; argument and
- * state errors are reported synchronously.  The library never allocates device
+ * device work is ordered on that stream and is asynchronous; argument and
+ * state errors are reported synchronously.  (For small layers a pass runs its two
+ * half-batches concurrently: the second half goes to a helper stream of the net,
+ * forked from and joined back into `stream` with events, so the caller sees
+ * ordinary stream order.)  The library never allocates device
  * memory: the caller hands in one workspace at sdnn_create and keeps it alive
  * until sdnn_destroy.
  *

@@ -142,7 +142,7 @@ struct SpmmArgs {
     float *out;           // [n_rows][B]
     const float *aux;     // MODE 0: bias [n_rows] (may be NULL); MODE 1: Xprev [n_rows][B]
     int32_t n_rows, B;
-    uint32_t n_tiles, n_rg, n_vblocks;
+    uint32_t n_tiles, n_rg, n_vblocks, tile_base;
     float cap;
     int32_t act;
 };
@@ -276,7 +276,7 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
         const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
         const RowMeta m = load_meta<MODE>(a.sched, a.idx, a.vals, a.perm, r, lane);
-        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile, lane);
+        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile + a.tile_base, lane);
     }
 }
 
@@ -540,6 +540,8 @@ struct sdnn_net {
     float *d_ping = nullptr, *d_pong = nullptr; // inference: two activation buffers
     int n_cu = 0;                 // compute units of the device
     int occ_spmm[2][3] = {{0, 0, 0}, {0, 0, 0}}; // resident workgroups per CU of k_spmm<V,MODE>
+    hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int state = ST_IDLE;
     int32_t B = 0;
     int32_t max_n = 0;
@@ -684,7 +686,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     net->cfg = *cfg;
     net->layers.resize(n_layers);
     char *base = (char *)d_workspace;
-    auto fail_free = [&](int code) { delete net; return code; };
+    auto fail_free = [&](int code) { sdnn_destroy(net); return code; };
 
     std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
     std::vector<int4> sched, t_sched;
@@ -757,6 +759,11 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         if (hipGetDevice(&devid) != hipSuccess || hipGetDeviceProperties(&prop, devid) != hipSuccess)
             return fail_free(fail(nullptr, SDNN_EHIP, "cannot query the device"));
         net->n_cu = prop.multiProcessorCount;
+        // default priority, like every stream here
+        if (hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&net->ev_fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&net->ev_join, hipEventDisableTiming) != hipSuccess)
+            return fail_free(fail(nullptr, SDNN_EHIP, "cannot create the side stream"));
     }
     if (cfg->training) {
         net->d_x0 = (float *)(base + pl.x0);
@@ -768,7 +775,24 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     return SDNN_OK;
 }
 
-extern "C" void sdnn_destroy(sdnn_net *net) { delete net; }
+extern "C" void sdnn_destroy(sdnn_net *net)
+{
+    if (!net) return;
+    if (net->side) { (void)hipStreamSynchronize(net->side); (void)hipStreamDestroy(net->side); }
+    if (net->ev_fork) (void)hipEventDestroy(net->ev_fork);
+    if (net->ev_join) (void)hipEventDestroy(net->ev_join);
+    delete net;
+}
+
+// Forward and backward treat the samples independently (the batch vectors are columns of X), so a
+// pass over small layers is run as two half-batches on two streams: each stream's kernels depend
+// only on its own previous kernel, and while one stream sits in the latencies at the head or tail
+// of a kernel, the other one computes.  Returns the samples per lane to use (0 = do not split).
+static int split_v(const sdnn_net *net, int B)
+{
+    if (B % 128 != 0 || (int64_t)net->max_n * B > ((int64_t)1 << 21)) return 0;
+    return B % 512 == 0 ? 4 : B % 256 == 0 ? 2 : 1; // two or more tiles of 64*V samples
+}
 
 static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
@@ -781,9 +805,11 @@ static int pick_v_spmm(int B, const void *a, const void *b, const void *c)
     return 1;
 }
 
+// part/n_parts: the batch tiles of the launch are the part-th of n_parts equal shares (n_parts = 2
+// when a pass is run as two independent half-batches on two streams); force_v: samples per lane, 0 = choose.
 template <int MODE>
 static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float *out,
-                       const float *aux, int B, hipStream_t stream)
+                       const float *aux, int B, hipStream_t stream, int part = 0, int n_parts = 1, int force_v = 0)
 {
     SpmmArgs a;
     if (MODE == 0) {
@@ -807,8 +833,11 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
         HIP_TRY(net, hipGetLastError());
         return SDNN_OK;
     }
-    const int V = pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
-    a.n_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
+    const int V = force_v ? force_v : pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
+    const uint32_t all_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
+    a.tile_base = all_tiles * (uint32_t)part / (uint32_t)n_parts;
+    a.n_tiles = all_tiles * (uint32_t)(part + 1) / (uint32_t)n_parts - a.tile_base;
+    if (a.n_tiles == 0) return SDNN_OK;
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     const uint64_t blocks = (uint64_t)a.n_tiles * a.n_rg;
     if (blocks > 0x7fffffffull) return fail(net, SDNN_EINVAL, "grid too large");
@@ -858,12 +887,24 @@ extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *
         if (bytes) HIP_TRY(net, hipMemcpyAsync(net->d_x0, d_X0, bytes, hipMemcpyDeviceToDevice, stream));
         in = net->d_x0;
     }
+    int sv = split_v(net, B);
+    if (sv > 1 && (!aligned(d_X0, 4 * sv) || (d_XL && !aligned(d_XL, 4 * sv)))) sv = 0;
+    if (sv) {
+        HIP_TRY(net, hipEventRecord(net->ev_fork, stream));
+        HIP_TRY(net, hipStreamWaitEvent(net->side, net->ev_fork, 0));
+    }
     for (int l = 0; l < L; ++l) {
         const LayerDev &d = net->layers[l];
         float *out = training ? d.X : (l == L - 1 ? d_XL : ((l & 1) ? net->d_pong : net->d_ping));
-        int rc = launch_spmm<0>(net, d, in, out, d.bias, B, stream);
+        int rc = sv ? launch_spmm<0>(net, d, in, out, d.bias, B, stream, 0, 2, sv)
+                    : launch_spmm<0>(net, d, in, out, d.bias, B, stream);
+        if (!rc && sv) rc = launch_spmm<0>(net, d, in, out, d.bias, B, net->side, 1, 2, sv);
         if (rc) return rc;
         in = out;
+    }
+    if (sv) {
+        HIP_TRY(net, hipEventRecord(net->ev_join, net->side));
+        HIP_TRY(net, hipStreamWaitEvent(stream, net->ev_join, 0));
     }
     if (training && d_XL) {
         const size_t bytes = 4 * (size_t)net->layers[L - 1].n_out * B;
@@ -896,11 +937,22 @@ extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
                            last.D, n, net->cfg.act_cap, net->cfg.activation);
         HIP_TRY(net, hipGetLastError());
     }
+    const int sv = split_v(net, B);
+    if (sv) {
+        HIP_TRY(net, hipEventRecord(net->ev_fork, stream));
+        HIP_TRY(net, hipStreamWaitEvent(net->side, net->ev_fork, 0));
+    }
     for (int l = L - 1; l >= 1; --l) {
         const LayerDev &d = net->layers[l];
         // Delta_{l} (0-based l-1) = (W^T Delta_{l+1}) masked by X_{l}
-        int rc = launch_spmm<1>(net, d, d.D, net->layers[l - 1].D, d.X_prev, B, stream);
+        int rc = sv ? launch_spmm<1>(net, d, d.D, net->layers[l - 1].D, d.X_prev, B, stream, 0, 2, sv)
+                    : launch_spmm<1>(net, d, d.D, net->layers[l - 1].D, d.X_prev, B, stream);
+        if (!rc && sv) rc = launch_spmm<1>(net, d, d.D, net->layers[l - 1].D, d.X_prev, B, net->side, 1, 2, sv);
         if (rc) return rc;
+    }
+    if (sv) {
+        HIP_TRY(net, hipEventRecord(net->ev_join, net->side));
+        HIP_TRY(net, hipStreamWaitEvent(stream, net->ev_join, 0));
     }
     net->state = ST_BACKWARD;
     return SDNN_OK;
