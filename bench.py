@@ -130,8 +130,10 @@ def main():
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "binding_unit": "vector L1 gather path (~30 B/clk/CU, see profiles/config2_counters.md)",
-                "launches_per_step": d_launches, "avg_launch_us": round(d_ms * 1e3 / d_launches, 3),
-                "bytes_per_launch": int(d_bytes / d_launches)}
+                "units_per_step": d_launches, "unit_of_work": "one layer" if dom != "update" else "all layers",
+                "avg_unit_us": round(d_ms * 1e3 / d_launches, 3), "bytes_per_unit": int(d_bytes / d_launches),
+                # forward/backward over small layers: each layer is two half-batch launches on two streams
+                "kernel_launches_per_unit": 2 if (dom != "update" and Bt % 128 == 0 and N * Bt <= 2 ** 21) else 1}
     net.close()
     del net
 

@@ -791,6 +791,10 @@ extern "C" void sdnn_destroy(sdnn_net *net)
 static int split_v(const sdnn_net *net, int B)
 {
     if (B % 128 != 0 || (int64_t)net->max_n * B > ((int64_t)1 << 21)) return 0;
+    // long rows (hundreds of entries) keep a wavefront busy for long: nothing to hide, and wider lanes pay more
+    int64_t nnz = 0, rows = 0;
+    for (const LayerDev &d : net->layers) { nnz += d.nnz; rows += d.n_out; }
+    if (nnz >= 128 * rows) return 0;
     return B % 512 == 0 ? 4 : B % 256 == 0 ? 2 : 1; // two or more tiles of 64*V samples
 }
 
