@@ -216,3 +216,23 @@ def test_paper_training_setup_one_vector_per_step():
             # carry the ORACLE's weights forward on the oracle side, the GPU keeps its own
             lay.values, lay.bias = v, b
     net.close()
+
+
+@pytest.mark.parametrize("training", [False, True])
+def test_two_stream_half_batches_match_oracle(training):
+    """B a multiple of 128 on small layers: forward (and backward) run as two half-batch chains on
+    two streams; inference mode shares the ping-pong buffers between them."""
+    work = wl.make_config(1, n=512, n_layers=9, b_infer=256, b_train=256, density=0.4)
+    ref = P.O32.forward(work.layers, work.x_infer, work.act_cap)
+    net = sdnn.Net(work.layers, work.act_cap, 256, training=training)
+    out = torch.empty(512, 256, device=P.DEV)
+    for _ in range(3):                       # repeated passes: the fork/join events are reused
+        out.zero_()
+        net.sdnn_forward(P.dev(work.x_infer), out)
+        assert np.array_equal(P.host(out), ref[-1])
+    if training:
+        g = P.gpu_train_step(work, work.x_train)
+        o = P.oracle_train_step(work, work.x_train)
+        st = P.compare_step(g, o, "split")
+        assert st["bitexact_d"] == 9 and st["live_g"] >= 6
+    net.close()
