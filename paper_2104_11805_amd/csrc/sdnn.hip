@@ -441,6 +441,11 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
             const int p = p0 + k;
             coff[k] = (size_t)(p < end ? L.col_idx[p] : L.col_idx[beg]) * ld;
         }
+        // the weight this lane will rewrite at the end of the chunk, requested now
+        const int kw = ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 + ((lane >> 1) & 1);
+        const bool writer = (lane & 1) == 0 && p0 + kw < end;
+        float w_old = 0.0f;
+        if (writer && !emit) w_old = L.vals[p0 + kw];
         double a[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = 0.0;
@@ -480,12 +485,10 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
             }
         }
         a[0] += __shfl_xor(a[0], 1);
-        const int k = ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 + ((lane >> 1) & 1);
-        const int p = p0 + k;
-        if ((lane & 1) == 0 && p < end) {
+        if (writer) {
             const float g = (float)a[0];
-            if (emit) g_out[p] = g;
-            else L.vals[p] = (float)((double)L.vals[p] - dlr * (double)g);
+            if (emit) g_out[p0 + kw] = g;
+            else L.vals[p0 + kw] = (float)((double)w_old - dlr * (double)g);
         }
     }
 }
