@@ -29,7 +29,8 @@
 // device helpers
 // ---------------------------------------------------------------------------
 
-#define WAVES_PER_BLOCK 4
+#define WAVES_PER_BLOCK 4 // product kernels: 4 rows per workgroup (measured best of 1, 2, 4, 8)
+#define UPD_WAVES 1       // update kernel: one row per workgroup (measured best of 1, 2, 4, 8)
 #define BLOCK_THREADS (64 * WAVES_PER_BLOCK)
 
 template <int V> __device__ __forceinline__ void ldv(const float *p, float (&x)[V]);
@@ -391,7 +392,7 @@ k_update_b1(const LayerDev *__restrict__ layers, int layer0, float lr, int updat
 //   emit == 1: g_out / gb_out receive the gradient of the single layer
 // ---------------------------------------------------------------------------
 template <int V>
-__global__ void __launch_bounds__(BLOCK_THREADS)
+__global__ void __launch_bounds__(64 * UPD_WAVES)
 k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int interleave, int B, float lr,
          int update_bias, int emit, float *__restrict__ g_out, float *__restrict__ gb_out)
 {
@@ -404,7 +405,7 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
     const LayerDev &L = layers[layer0 + layer_rel];
     const int lane = threadIdx.x & 63;
     const unsigned rgi = interleave ? (blockIdx.x >> 3) : blockIdx.x;
-    const int r = __builtin_amdgcn_readfirstlane((int)(rgi * WAVES_PER_BLOCK + (threadIdx.x >> 6)));
+    const int r = __builtin_amdgcn_readfirstlane((int)(rgi * UPD_WAVES + (threadIdx.x >> 6)));
     if (r >= L.n_out) return;
     const int4 task = L.sched[r];
     const int row = task.x, beg = task.y, end = task.z;
@@ -989,17 +990,17 @@ static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int 
     }
     // all activation / delta buffers are 256-byte aligned; rows are aligned iff B % 4 == 0
     const int V = pick_v_update(B, net->layers[layer0].D, net->layers[layer0].X_prev);
-    const unsigned n_rg = (unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    const unsigned n_rg = (unsigned)((max_rows + UPD_WAVES - 1) / UPD_WAVES);
     // with many layers, interleave them over the XCDs (one L2 per layer); with few, keep all XCDs on each layer
     const int interleave = n_layers >= 64;
     for (int l0 = 0; l0 < n_layers; l0 += 65535) {
         const int nl = std::min(65535, n_layers - l0);
         dim3 grid(interleave ? 8u * n_rg : n_rg, (unsigned)(interleave ? (nl + 7) / 8 : nl));
         if (V == 4)
-            hipLaunchKernelGGL(k_update<4>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
+            hipLaunchKernelGGL(k_update<4>, grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
                                layer0 + l0, nl, interleave, B, lr, net->cfg.update_bias, emit, g, gb);
         else
-            hipLaunchKernelGGL(k_update<1>, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers,
+            hipLaunchKernelGGL(k_update<1>, grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
                                layer0 + l0, nl, interleave, B, lr, net->cfg.update_bias, emit, g, gb);
         HIP_TRY(net, hipGetLastError());
     }
