@@ -68,7 +68,13 @@ def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+            # nothing built yet: compile once (hipcc cross-compiles for gfx950 without a GPU); no fallback exists
+            try:
+                from . import build as _build
+                _build.build_lib()
+            except Exception as e:
+                raise ImportError(f"{LIB_PATH} is missing and could not be built ({e}): run "
+                                  "`python -c 'import __graft_entry__ as g; g.build()'`") from e
         l = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(l, name)
