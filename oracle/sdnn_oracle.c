@@ -60,7 +60,7 @@ static inline double act_deriv_from_output(int kind, double x, double cap) {
     return (x > 0.0 && x < cap) ? 1.0 : 0.0;
 }
 
-/* Eq. 3 / Algorithm 1 lines 3-4, batch form:  Xout = f(W Xin + b 1^T).
+/* Eq. 3 / Algorithm 1 (feed-forward step), batch form:  Xout = f(W Xin + b 1^T).
  * z(j,s) = sum over the stored entries of row j, in storage order. */
 void FN(oracle_forward_layer)(int32_t n_out, const int32_t *row_ptr, const int32_t *col_idx,
                               const REAL *vals, const REAL *bias, const REAL *Xin, int32_t B,
@@ -78,7 +78,7 @@ void FN(oracle_forward_layer)(int32_t n_out, const int32_t *row_ptr, const int32
     }
 }
 
-/* Eq. 6 / Algorithm 1 line 5:  delta^L = grad_{x^L} J  (.)  f'(z^L). */
+/* Eq. 6 / Algorithm 1 (output-layer delta):  delta^L = grad_{x^L} J  (.)  f'(z^L). */
 void FN(oracle_output_delta)(int32_t n, int32_t B, const REAL *dLoss, const REAL *XL, int kind,
                              double cap, REAL *DL)
 {
@@ -86,7 +86,7 @@ void FN(oracle_output_delta)(int32_t n, int32_t B, const REAL *dLoss, const REAL
         DL[e] = (REAL)((double)dLoss[e] * act_deriv_from_output(kind, (double)XL[e], cap));
 }
 
-/* Eq. 7 / Algorithm 1 line 7:  Dprev = (W^T D) (.) f'(z_prev).
+/* Eq. 7 / Algorithm 1 (delta propagation):  Dprev = (W^T D) (.) f'(z_prev).
  * Written as the sparse AXPY form of Section 5 (s(i) += W(j,i) delta(j) for
  * every stored entry), rows j visited in ascending order, so that each s(i)
  * adds its terms by ascending j.  No transposed copy of W is built.
@@ -111,7 +111,7 @@ void FN(oracle_backward_layer)(int32_t n_out, int32_t n_in, const int32_t *row_p
     free(S);
 }
 
-/* Eq. 4 / Algorithm 1 line 8, confined to the stored entries of W and summed
+/* Eq. 4 / Algorithm 1 (weight gradient), confined to the stored entries of W and summed
  * over the samples of the batch:  g(p) = sum_s delta(j,s) x_prev(i,s) for the
  * p-th stored entry (j,i);  bias gradient gb(j) = sum_s delta(j,s) (the bias
  * is the weight of a link from a constant-1 neuron, Section 3.2). */
@@ -134,7 +134,7 @@ void FN(oracle_weight_grad)(int32_t n_out, const int32_t *row_ptr, const int32_t
     }
 }
 
-/* Eq. 5 / Algorithm 1 line 9 on an array of parameters:  w <- w - eta * g. */
+/* Eq. 5 / Algorithm 1 (descent step) on an array of parameters:  w <- w - eta * g. */
 void FN(oracle_sgd_apply)(size_t n, REAL *w, const REAL *g, double lr)
 {
     for (size_t e = 0; e < n; ++e)

@@ -1,7 +1,7 @@
 """CPU oracle driver: TEST INFRASTRUCTURE ONLY (tests, smoke check, CPU baseline).
 
-Walks the layers in the order of Algorithm 1 (feed-forward lines 2-4, output
-delta line 5, the backward loop lines 6-9) and calls the plain C routines of
+Walks the layers in the order of Algorithm 1 (feed-forward sweep, output
+delta, then the backward loop over the layers) and calls the plain C routines of
 sdnn_oracle.c for every per-layer operation.  Nothing here is shared with the
 HIP library, and nothing here may be imported by it.
 
@@ -143,7 +143,7 @@ class Oracle:
 
     def backward(self, layers: Sequence, xs: List[np.ndarray], dloss: np.ndarray,
                  cap: float) -> List[Optional[np.ndarray]]:
-        """Line 5 and line 7 for k = L..2: returns [None, Delta_1, ..., Delta_L]."""
+        """Output delta (Eq. 6), then Eq. 7 for k = L..2: returns [None, Delta_1, ..., Delta_L]."""
         L = len(layers)
         deltas: List[Optional[np.ndarray]] = [None] * (L + 1)
         deltas[L] = self.output_delta(dloss, xs[L], cap)
