@@ -107,7 +107,13 @@ def main():
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in marks) / len(marks)
     bwd_ms = sum(e[1].elapsed_time(e[2]) for e in marks) / len(marks)
     upd_ms = sum(e[2].elapsed_time(e[3]) for e in marks) / len(marks)
+    per_step = sorted(e[0].elapsed_time(e[3]) for e in marks)       # event time of each single step
     train_eps = nnz_total * Bt / (ms_step * 1e-3)
+    # share of non-zero activations after layers 1, 2 and L of the minibatch (the nominal inputs of configs 1-4
+    # die out after the first layers; the kernels never skip zeros, so the timing does not profit from it)
+    net.sdnn_forward(x0, xl)
+    active = {f"layer_{k}": round(float((net.sdnn_get_activation(k, Bt) != 0).float().mean()), 4)
+              for k in sorted({1, min(2, L), L})}
 
     # ---- roofline of the dominant kernel --------------------------------
     fb = bb = ub = 0
@@ -188,16 +194,28 @@ def main():
         cpu = {"value": sum(l.nnz for l in sub) * Bt / cs, "unit": "edges/s", "cores": orc.threads(),
                "kind": "oracle",
                "sample": f"one training step on the first {Ls} of {L} layers, full minibatch {Bt} ({cs:.1f} s)"}
+        # the same oracle on one thread, on a shorter depth prefix (about 1.5e9 edge visits)
+        n_all = orc.threads()
+        L1 = int(max(1, min(Ls, 1.5e9 // per_layer)))
+        orc.set_threads(1)
+        t0 = time.perf_counter()
+        orc.train_step(work.layers[:L1], work.x_train, work.act_cap, dfn, work.lr)
+        c1 = time.perf_counter() - t0
+        orc.set_threads(n_all)
+        cpu["single_thread"] = {"value": sum(l.nnz for l in work.layers[:L1]) * Bt / c1, "unit": "edges/s",
+                                "sample": f"first {L1} layers ({c1:.1f} s)"}
 
     out = {
         "metric": "edges/s, forward+backward+SGD step (nnz x samples / time)",
         "value": train_eps, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(ms_step, 4), "step_ms_min": round(per_step[0], 4),
+        "step_ms_median": round(per_step[len(per_step) // 2], 4), "edge_visits_per_s": 3.0 * train_eps,
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"config {args.config}: N={N}, L={L}, 32 nnz/row" if args.config < 5
                    else f"config 5: N={N}, L={L}, heavy-tailed rows",
                    "train_batch": Bt, "infer_samples": Bi, "total_nnz": nnz_total,
-                   "storage": "fp32", "accumulate": "fp64", "input_density": work.meta.get("density")},
+                   "storage": "fp32", "accumulate": "fp64", "input_density": work.meta.get("density"), "active_fraction": active},
         "pass_ms": {"forward": round(fwd_ms, 4), "backward": round(bwd_ms, 4), "update": round(upd_ms, 4)},
         "inference": infer, "roofline": roofline, "cpu_baseline": cpu,
         "setup_s": {"generate": round(gen_s, 2)},

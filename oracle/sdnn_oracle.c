@@ -37,8 +37,11 @@
 #ifdef _OPENMP
 #include <omp.h>
 int FN(oracle_threads)(void) { return omp_get_max_threads(); }
+/* Thread count of the following calls (timing only; results do not depend on it). */
+void FN(oracle_set_threads)(int n) { if (n > 0) omp_set_num_threads(n); }
 #else
 int FN(oracle_threads)(void) { return 1; }
+void FN(oracle_set_threads)(int n) { (void)n; }
 #endif
 
 #include <math.h>

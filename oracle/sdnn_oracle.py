@@ -64,6 +64,10 @@ class Oracle:
     def threads(self) -> int:
         return int(self._fn("oracle_threads")())
 
+    def set_threads(self, n: int) -> None:
+        """Thread count of the following calls (for timing; the results do not depend on it)."""
+        self._fn("oracle_set_threads")(int(n))
+
     def _arr(self, a):
         return np.ascontiguousarray(a, dtype=self.dtype)
 
