@@ -296,8 +296,12 @@ __global__ void __launch_bounds__(256) k_output_delta(const float *__restrict__ 
 // ---------------------------------------------------------------------------
 // One sample per step (B = 1, the paper's own training experiments: one input
 // vector per SGD step, Section 6.1).  Lanes over samples would idle 63 of 64
-// lanes, so here a lane owns a whole row and walks it in storage order (same
-// sum as everywhere else); the activation vector is a few KB and lives in L1/L2.
+// lanes, so there are three products of their own, all taking each row's sum in
+// storage order (same result as everywhere else):
+//   k_spmv_stage  wide layers with short rows: lanes over a contiguous stretch of entries,
+//                 products parked in LDS, then a lane per row adds them up;
+//   k_spmv_wave   narrow layers, or long rows up to 16384 rows: a wavefront per row;
+//   k_spmv        the rest (wide layers with long rows): a lane per row.
 // ---------------------------------------------------------------------------
 template <int MODE>
 __global__ void __launch_bounds__(256) k_spmv(const SpmmArgs a)
@@ -358,25 +362,96 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmv_wave(const SpmmArgs a)
     }
 }
 
-// Update for B = 1: no sum over samples, so the lanes of a wavefront take the
-// entries of its row: vals[p] -= lr * delta(row) * x(col[p]); lane 0 does the bias.
+// Wide layers at B = 1: a 64-lane workgroup owns R consecutive rows, whose entries are one contiguous
+// stretch of the index arrays.  All lanes walk that stretch together (coalesced index and value
+// loads, one gathered activation per entry) and park the products w*x, which are exact in fp64, in
+// LDS; then lane r adds the products of row r in storage order, the same sum as everywhere else.
+// The stretch is taken in segments of SPMV_STAGE entries, so rows of any length work.
+#define SPMV_STAGE 1024
+#define SPMV_STAGE_MIN_ROWS 2048 // below this a wavefront per row is as fast (measured)
+template <int MODE, int J>
+__global__ void __launch_bounds__(64) k_spmv_stage(const SpmmArgs a, int R)
+{
+    __shared__ double prod[SPMV_STAGE + SPMV_STAGE / 32]; // one pad per 32 entries: lanes that start 32 apart hit different banks
+    const int lane = threadIdx.x;
+    const int r0 = blockIdx.x * R;
+    const int nr = min(R, a.n_rows - r0); // >= 1 by the grid size
+    const int row = r0 + lane;
+    int p = 0, end = 0;
+    if (lane < nr) { p = a.row_ptr[row]; end = a.row_ptr[row + 1]; }
+    const int e0 = a.row_ptr[r0], e1 = a.row_ptr[r0 + nr];
+    double acc = 0.0;
+    for (int sb = e0; sb < e1; sb += SPMV_STAGE) {
+        const int se = min(sb + SPMV_STAGE, e1);
+        for (int j0 = 0; j0 * 64 < se - sb; j0 += J) {
+            int c[J];
+            float w[J], x[J];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const int e = sb + (j0 + j) * 64 + lane;
+                c[j] = -1;
+                if (e < se) {
+                    c[j] = a.idx[e];
+                    w[j] = MODE == 1 ? a.vals[a.perm[e]] : a.vals[e];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < J; ++j)
+                if (c[j] >= 0) x[j] = a.in[c[j]];
+#pragma unroll
+            for (int j = 0; j < J; ++j)
+                if (c[j] >= 0) {
+                    const int q = (j0 + j) * 64 + lane;
+                    prod[q + (q >> 5)] = (double)w[j] * (double)x[j];
+                }
+        }
+        __syncthreads();
+        const int pe = min(end, se); // my row's entries inside this segment are [p, pe)
+        if (p < pe) {
+            for (; p < pe; p += 4) { // four parked products requested together, added one after the other
+                double v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int q = min(p + k, pe - 1) - sb;
+                    v[k] = prod[q + (q >> 5)];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (p + k < pe) acc += v[k];
+            }
+            p = pe;
+        }
+        __syncthreads();
+    }
+    if (lane < nr) {
+        if (MODE == 0) a.out[row] = act_apply(a.act, acc + (a.aux ? (double)a.aux[row] : 0.0), a.cap);
+        else a.out[row] = act_backprop(a.act, acc, a.aux[row], a.cap);
+    }
+}
+
+// Update for B = 1: no sum over samples, so the lanes take the entries of the rows:
+// vals[p] -= lr * delta(row) * x(col[p]).  A wavefront holds 64 >> lpr_log2 rows of 1 << lpr_log2
+// lanes each (chosen from the mean row length, so that short rows do not idle half the lanes);
+// the first lane of a row does its bias.
 __global__ void __launch_bounds__(BLOCK_THREADS)
-k_update_b1(const LayerDev *__restrict__ layers, int layer0, float lr, int update_bias, int emit,
+k_update_b1(const LayerDev *__restrict__ layers, int layer0, int lpr_log2, float lr, int update_bias, int emit,
             float *__restrict__ g_out, float *__restrict__ gb_out)
 {
     const LayerDev &L = layers[layer0 + blockIdx.y];
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    const int lpr = 1 << lpr_log2;
+    const int l = lane & (lpr - 1);
+    const int row = ((blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6)) << (6 - lpr_log2)) + (lane >> lpr_log2);
     if (row >= L.n_out) return;
     const int beg = L.row_ptr[row], end = L.row_ptr[row + 1];
     const float d = L.D[row];
     const double dlr = (double)lr;
-    for (int p = beg + lane; p < end; p += 64) {
+    for (int p = beg + l; p < end; p += lpr) {
         const float g = (float)((double)d * (double)L.X_prev[L.col_idx[p]]);
         if (emit) { if (g_out) g_out[p] = g; }
         else L.vals[p] = (float)((double)L.vals[p] - dlr * (double)g);
     }
-    if (lane == 0) {
+    if (l == 0) {
         if (emit) { if (gb_out) gb_out[row] = d; }
         else if (update_bias) L.bias[row] = (float)((double)L.bias[row] - dlr * (double)d);
     }
@@ -833,7 +908,12 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     if (a.in_bytes >= ((size_t)1 << 32))
         return fail(net, SDNN_EINVAL, "activation block of %zu bytes exceeds 4 GiB: use a smaller B", a.in_bytes);
     if (B == 1) {
-        if (a.n_rows <= 16384) // a wavefront per row while that still fits the chip a few times over (measured crossover)
+        const int64_t nnz = d.nnz;
+        if (a.n_rows >= SPMV_STAGE_MIN_ROWS && nnz < 128 * (int64_t)a.n_rows) {
+            // short rows, wide layer: R consecutive rows per 64-lane workgroup (measured: 8, and 16 from 32768 rows)
+            const int R = a.n_rows >= 32768 ? 16 : 8;
+            hipLaunchKernelGGL((k_spmv_stage<MODE, 8>), dim3((unsigned)((a.n_rows + R - 1) / R)), dim3(64), 0, stream, a, R);
+        } else if (a.n_rows <= 16384) // a wavefront per row while that still fits the chip a few times over
             hipLaunchKernelGGL(k_spmv_wave<MODE>, dim3((unsigned)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK)),
                                dim3(BLOCK_THREADS), 0, stream, a);
         else
@@ -979,11 +1059,17 @@ static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int 
     if (max_rows == 0) return SDNN_OK;
     const int B = net->B;
     if (B == 1) {
+        // lanes per row: the power of two that covers the mean row length, 8..64
+        int64_t nnz = 0, rows = 0;
+        for (int l = layer0; l < layer0 + n_layers; ++l) { nnz += net->layers[l].nnz; rows += net->layers[l].n_out; }
+        int lpr_log2 = 3;
+        while (lpr_log2 < 6 && ((int64_t)rows << lpr_log2) < nnz) ++lpr_log2;
+        const int rows_per_block = WAVES_PER_BLOCK << (6 - lpr_log2);
         for (int l0 = 0; l0 < n_layers; l0 += 65535) {
             const int nl = std::min(65535, n_layers - l0);
-            dim3 grid((unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), (unsigned)nl);
-            hipLaunchKernelGGL(k_update_b1, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers, layer0 + l0, lr,
-                               net->cfg.update_bias, emit, g, gb);
+            dim3 grid((unsigned)((max_rows + rows_per_block - 1) / rows_per_block), (unsigned)nl);
+            hipLaunchKernelGGL(k_update_b1, grid, dim3(BLOCK_THREADS), 0, stream, net->d_layers, layer0 + l0, lpr_log2,
+                               lr, net->cfg.update_bias, emit, g, gb);
             HIP_TRY(net, hipGetLastError());
         }
         return SDNN_OK;

@@ -160,6 +160,25 @@ def random_layer(seed: int, n_out: int, n_in: int, density: float, scale: float 
     return Layer(n_out, n_in, row_ptr, col_idx, values, bias)
 
 
+def ragged_layer(seed: int, n_out: int, n_in: int, density: float, n_long_rows: int, long_row_len: int,
+                 n_long_cols: int, long_col_len: int, scale: float = 0.3) -> Layer:
+    """Test layer with a few very long rows and a few very long columns in a sea of short ones
+    (and some empty rows): a sparse Bernoulli pattern plus randomly placed dense stretches."""
+    rng = np.random.default_rng(seed)
+    mask = rng.random((n_out, n_in)) < density
+    for r in rng.choice(n_out, size=n_long_rows, replace=False):
+        mask[r, rng.choice(n_in, size=long_row_len, replace=False)] = True
+    for c in rng.choice(n_in, size=n_long_cols, replace=False):
+        mask[rng.choice(n_out, size=long_col_len, replace=False), c] = True
+    counts = mask.sum(axis=1)
+    row_ptr = np.zeros(n_out + 1, dtype=np.int32)
+    np.cumsum(counts, out=row_ptr[1:])
+    col_idx = np.nonzero(mask)[1].astype(np.int32)
+    values = (rng.standard_normal(col_idx.size) * scale / np.sqrt(np.maximum(counts, 1)).repeat(counts)).astype(np.float32)
+    bias = (rng.standard_normal(n_out) * 0.1).astype(np.float32)
+    return Layer(n_out, n_in, row_ptr, col_idx, values, bias)
+
+
 # ----------------------------------------------------------------------------
 # inputs and targets
 # ----------------------------------------------------------------------------

@@ -236,3 +236,60 @@ def test_two_stream_half_batches_match_oracle(training):
         st = P.compare_step(g, o, "split")
         assert st["bitexact_d"] == 9 and st["live_g"] >= 6
     net.close()
+
+
+@pytest.mark.parametrize("activation", ["relu", "sigmoid"])
+def test_one_vector_wide_layers_take_the_staged_kernels(activation):
+    """B = 1 on layers of 2000+ rows with short uneven rows (Bernoulli pattern, some rows empty): the
+    products are formed by all lanes over a contiguous stretch of entries and summed per row in
+    storage order; row counts that are no multiple of the rows per workgroup."""
+    work = wl.tiny_net(61, sizes=(3000, 2500, 4100, 2049), density=0.01, b=1)
+    work.activation = activation
+    lens = np.concatenate([np.diff(l.row_ptr) for l in work.layers])
+    assert lens.min() <= 12 and lens.max() >= 50
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05)
+    st = P.compare_step(g, o, f"staged b=1 {activation}", exact_fwd=(activation == "relu"))
+    assert st["live_g"] == 3 and st["live_d"] == 3
+    if activation == "relu":
+        assert st["bitexact_d"] == 3
+
+
+def test_one_vector_rows_longer_than_a_stage():
+    """B = 1, rows and columns of 2500-3000 entries (several staging segments each) among rows of
+    about three entries, in both orientations."""
+    layers = [wl.ragged_layer(7101, 2300, 5000, 0.0006, 3, 2700, 4, 2000),
+              wl.ragged_layer(7102, 4200, 2300, 0.0012, 2, 2200, 3, 3000)]
+    for l in layers:
+        assert l.nnz < 128 * l.n_out and np.diff(l.row_ptr).max() > 2048 and np.diff(l.row_ptr).min() <= 1
+    x = wl.normal_inputs(7190, 5000, 1)
+    tg = wl.uniform_targets(7191, 4200, 1)
+    work = wl.Workload("ragged-b1", layers, float("inf"), x, 1, "mse", 0.01, targets=tg)
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05)
+    st = P.compare_step(g, o, "ragged b=1")
+    assert st["bitexact_d"] == 2 and st["live_g"] == 2
+
+
+def test_paper_training_setup_wide_net_two_steps():
+    """The paper's setup (sigmoid, U[-1,1] weights, one vector per step) at N = 4096, where B = 1
+    takes the staged product kernels and the two-rows-per-wavefront update."""
+    work = wl.paper_training_setup(4096, n_layers=5, n_inputs=2)
+    orc = P.ORACLES["sigmoid"]
+    net = sdnn.Net(work.layers, work.act_cap, 1, training=True, activation="sigmoid")
+    layers = work.layers
+    for s in range(2):
+        x0 = np.ascontiguousarray(work.x_infer[:, s:s + 1])
+        y = np.ascontiguousarray(work.targets[:, s:s + 1])
+        xl = torch.empty(4096, 1, device=P.DEV)
+        net.sdnn_forward(P.dev(x0), xl)
+        net.sdnn_backward(sdnn.sdnn_mse_dloss(xl, P.dev(y)))
+        net.sdnn_sgd_step(work.lr)
+        xs, deltas, grads, new = orc.train_step(layers, x0, work.act_cap, lambda x: P.mse_dloss(x, y), work.lr)
+        P.assert_forward_close(P.host(xl), xs[-1], f"step {s} X_L")
+        for k, (lay, (v, b)) in enumerate(zip(layers, new)):
+            gv, gb = (P.host(t) for t in net.sdnn_get_weights(k + 1))
+            P.assert_grad_close(gv, v, f"step {s} layer {k + 1} weights")
+            P.assert_grad_close(gb, b, f"step {s} layer {k + 1} bias")
+            lay.values, lay.bias = v, b
+    net.close()
