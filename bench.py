@@ -43,6 +43,8 @@ def main():
                     help="the paper's own training experiment: sigmoid, weights U[-1,1], one input vector per step")
     ap.add_argument("--n", type=int, default=1024, help="neurons per layer for --paper-setup")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--check-every", type=int, default=4,
+                    help="layers between two packings of the live samples in the skip-dead inference figure")
     ap.add_argument("--no-inference", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -170,6 +172,31 @@ def main():
         infer = {"edges_per_s": nnz_total * Bi / (ims * 1e-3), "ms": round(ims, 3), "samples": Bi,
                  "block": block, "algorithmic_GBs": round(ibytes / (ims * 1e-3) / 1e9, 1),
                  "hbm_frac": round(ibytes / (ims * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # second figure, never the headline: the same inference with dead samples dropped (ReLU, biases <= 0);
+        # the edge count in the numerator then includes edges that were never visited
+        if work.activation == "relu" and all((l.bias <= 0).all() for l in work.layers[1:]):
+            n_live = torch.zeros(1, dtype=torch.int32, device=dev)
+            xchk = [torch.empty_like(o) for o in xout]
+
+            def skip_pass(outs):
+                for a, o in zip(xin, outs):
+                    inet.sdnn_forward_skip_dead(a, o, check_every=args.check_every, n_live=n_live)
+
+            skip_pass(xchk)
+            same = all(torch.equal(a, b) for a, b in zip(xout, xchk))
+            live_end = 0
+            for a, o in zip(xin, xchk):
+                inet.sdnn_forward_skip_dead(a, o, check_every=args.check_every, n_live=n_live)
+                live_end += int(n_live.item())
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(k):
+                skip_pass(xchk)
+            torch.cuda.synchronize()
+            sms = (time.perf_counter() - t0) * 1e3 / k
+            infer["skip_dead"] = {"edges_per_s": nnz_total * Bi / (sms * 1e-3), "ms": round(sms, 3),
+                                  "check_every": args.check_every, "live_samples_at_last_check": live_end,
+                                  "identical_to_plain_forward": bool(same)}
         inet.close()
         del inet
 

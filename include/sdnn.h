@@ -106,6 +106,19 @@ void sdnn_destroy(sdnn_net *net);
  * In training mode X_0..X_L are kept in the workspace (X_0 is copied). */
 int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream);
 
+/* The same result as sdnn_forward on an inference net (training = 0), computed without the samples
+ * that have died: with the clamped ReLU and biases <= 0, a sample whose activations are all zero
+ * after some layer stays zero in every later layer (Eq. 3 with x = 0 gives f(b) = 0), so its column
+ * is dropped.  After every check_every-th layer (>= 1) the live columns are packed to the front of
+ * the block on the device; no host synchronisation.  Needs SDNN_ACT_RELU_CAP and every bias of
+ * layers 2..L <= 0 as passed to sdnn_create (SDNN_ESTATE otherwise, also after sdnn_set_weights
+ * replaced such a bias); B <= 8192 (SDNN_EINVAL otherwise); with B = 1 nothing is packed.
+ * d_n_live: NULL, or device int32[1] that receives the number of samples still live after the
+ * last check.  The throughput of this call counts edges that were never visited and is reported
+ * apart from that of sdnn_forward. */
+int sdnn_forward_skip_dead(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL,
+                           int32_t check_every, int32_t *d_n_live, void *stream);
+
 /* Eqs. 6-7.  d_dLoss [n_out(L)][B] = dJ/dX_L of the caller's loss, B as in the
  * forward call that must directly precede it.  Training mode only. */
 int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream);

@@ -146,6 +146,8 @@ struct SpmmArgs {
     uint32_t n_tiles, n_rg, n_vblocks, tile_base;
     float cap;
     int32_t act;
+    const int32_t *n_live; // NULL, or the number of leading columns of the block that still matter (device)
+    int32_t *flags;        // NULL, or MODE 0: flags[s] is set to 1 for every sample s with a non-zero output
 };
 
 // The part of a row task that does not depend on the previous layer's output:
@@ -189,7 +191,7 @@ template <int V, int MODE, int U>
 __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const float *vals,
                                          const int32_t *perm, const float *in, size_t in_bytes,
                                          float *out, const float *aux, int B, float capf, int act,
-                                         unsigned tile, int lane)
+                                         unsigned tile, int lane, int32_t *flags)
 {
     const int s_own = (int)tile * (64 * V) + lane * V;
     const bool live = s_own < B;
@@ -260,6 +262,11 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
         for (int v = 0; v < V; ++v) o[v] = act_backprop(act, acc[v], xp[v], capf);
     }
     if (live) stv<V>(out + (size_t)m.row * ld + s, o);
+    if (MODE == 0 && flags != nullptr && live) { // other rows store the same 1: no ordering needed
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            if (o[v] != 0.0f) flags[s + v] = 1;
+    }
 }
 
 // The grid is sized to what the chip holds at once and every workgroup walks
@@ -271,13 +278,18 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
 {
     const int lane = threadIdx.x & 63;
     const unsigned wave = threadIdx.x >> 6;
-    for (unsigned vb = blockIdx.x; vb < a.n_vblocks; vb += gridDim.x) {
+    unsigned n_tiles = a.n_tiles, n_vblocks = a.n_vblocks;
+    if (a.n_live) { // only the batch tiles that hold live columns
+        n_tiles = min(n_tiles, ((unsigned)*a.n_live + 64u * V - 1u) / (64u * V));
+        n_vblocks = n_tiles * a.n_rg;
+    }
+    for (unsigned vb = blockIdx.x; vb < n_vblocks; vb += gridDim.x) {
         unsigned tile, rg;
-        map_block(vb, a.n_tiles, a.n_rg, tile, rg);
+        map_block(vb, n_tiles, a.n_rg, tile, rg);
         const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
         const RowMeta m = load_meta<MODE>(a.sched, a.idx, a.vals, a.perm, r, lane);
-        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile + a.tile_base, lane);
+        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile + a.tile_base, lane, a.flags);
     }
 }
 
@@ -570,6 +582,98 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
 }
 
 // ---------------------------------------------------------------------------
+// Inference that drops dead samples.  With ReLU and biases <= 0 a sample whose activations are all
+// zero after some layer stays all zero in every later layer, so its column need not be computed any
+// more.  Every few layers the live columns of the activation block are moved to the front (in
+// order) and the product kernels are told how many columns still matter; the count lives in device
+// memory, so nothing waits for the host.  map[c] remembers which sample sits in column c.
+// ---------------------------------------------------------------------------
+#define LIVE_ROWS 64  // rows per workgroup of the final scatter
+#define PACK_ROWS 16  // rows per workgroup of k_pack
+#define PACK_MAX_B 8192
+
+// map = identity, both flag arrays cleared, n_live = B
+__global__ void __launch_bounds__(256) k_skip_init(int32_t *__restrict__ map, int32_t *__restrict__ flags0,
+                                                   int32_t *__restrict__ flags1, int32_t *__restrict__ n_live, int B)
+{
+    for (int s = blockIdx.x * 256 + threadIdx.x; s < B; s += gridDim.x * 256) { map[s] = s; flags0[s] = 0; flags1[s] = 0; }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_live = B;
+}
+
+// Packs the flagged columns of X [n_rows][ld] to the front, in order and in place.  Every workgroup
+// derives the new position of each column from the flags by itself (a prefix sum over at most
+// PACK_MAX_B flags) and then moves its own rows: a wavefront walks a row in chunks of 64 columns,
+// front to back; a chunk is read completely before any of it is written and lands at or before its
+// own place, so nothing unread is overwritten.  Workgroup 0 also writes the state of the next
+// round, which nobody reads during this launch: the sample ids of the packed columns, the new
+// count, and a cleared flag array.  If no column died nothing moves.
+__global__ void __launch_bounds__(256) k_pack(float *X, int n_rows, int ld, const int32_t *__restrict__ flags,
+                                              const int32_t *__restrict__ n_live_in, const int32_t *__restrict__ map_in,
+                                              int32_t *__restrict__ n_live_out, int32_t *__restrict__ map_out,
+                                              int32_t *__restrict__ flags_next)
+{
+    __shared__ int32_t newpos[PACK_MAX_B];
+    __shared__ int wave_sum[4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int nl = *n_live_in;
+    const int per = (nl + 255) / 256;
+    const int c0 = min(t * per, nl), c1 = min(c0 + per, nl);
+    int cnt = 0;
+    for (int c = c0; c < c1; ++c) cnt += flags[c] != 0;
+    int x = cnt; // inclusive prefix sum over the 256 threads
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    if (lane == 63) wave_sum[wave] = x;
+    __syncthreads();
+    int before = 0, nl_new = 0;
+    for (int w = 0; w < 4; ++w) {
+        const int v = wave_sum[w];
+        if (w < wave) before += v;
+        nl_new += v;
+    }
+    int pos = before + x - cnt;
+    for (int c = c0; c < c1; ++c) newpos[c] = flags[c] != 0 ? pos++ : -1;
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        for (int c = c0; c < c1; ++c)
+            if (newpos[c] >= 0) map_out[newpos[c]] = map_in[c];
+        for (int c = t; c < ld; c += 256) flags_next[c] = 0;
+        if (t == 0) *n_live_out = nl_new;
+    }
+    if (nl_new == nl) return;
+    const int r_end = min(n_rows, ((int)blockIdx.x + 1) * PACK_ROWS);
+    for (int r = (int)blockIdx.x * PACK_ROWS + wave; r < r_end; r += 4) {
+        float *row = X + (size_t)r * ld;
+        for (int cb = 0; cb < nl; cb += 64) {
+            const int c = cb + lane;
+            int np = -1;
+            float v = 0.0f;
+            if (c < nl) { np = newpos[c]; v = row[c]; }
+            if (np >= 0) row[np] = v;
+        }
+    }
+}
+
+// XL[r][map[c]] = X[r][c] for c < n_live (the other columns of XL were zeroed before)
+__global__ void __launch_bounds__(256) k_scatter_cols(const float *__restrict__ X, float *__restrict__ XL, int n,
+                                                      int ld, const int32_t *__restrict__ map,
+                                                      const int32_t *__restrict__ n_live)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= *n_live) return;
+    const int dc = map[c];
+    const int r0 = blockIdx.y * LIVE_ROWS, r1 = min(n, r0 + LIVE_ROWS);
+    for (int r = r0; r < r1; ++r) XL[(size_t)r * ld + dc] = X[(size_t)r * ld + c];
+}
+
+__global__ void __launch_bounds__(256) k_fill_f32(float *__restrict__ p, size_t n, float v)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) p[e] = v;
+}
+
+// ---------------------------------------------------------------------------
 // loss-gradient helpers
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_mse_dloss(const float *__restrict__ x,
@@ -621,6 +725,8 @@ struct sdnn_net {
     int occ_spmm[2][3] = {{0, 0, 0}, {0, 0, 0}}; // resident workgroups per CU of k_spmm<V,MODE>
     hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int32_t *d_flags[2] = {nullptr, nullptr}, *d_map[2] = {nullptr, nullptr}, *d_n_live[2] = {nullptr, nullptr}; // inference: dead-sample skipping, two rounds' state
+    bool bias_nonpos = false;     // every bias of layers 2..L is <= 0 (as uploaded; cleared when a bias is replaced)
     int state = ST_IDLE;
     int32_t B = 0;
     int32_t max_n = 0;
@@ -659,7 +765,7 @@ struct Plan {
         size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D;
     };
     std::vector<PerLayer> pl;
-    size_t table = 0, x0 = 0, ping = 0, pong = 0, total = 0;
+    size_t table = 0, x0 = 0, ping = 0, pong = 0, flags[2] = {0, 0}, map[2] = {0, 0}, n_live[2] = {0, 0}, total = 0;
 };
 
 static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg)
@@ -717,6 +823,11 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
     } else {
         pl.ping = take(4 * max_n * mb);
         pl.pong = take(4 * max_n * mb);
+        for (int k = 0; k < 2; ++k) {
+            pl.flags[k] = take(4 * mb);
+            pl.map[k] = take(4 * mb);
+            pl.n_live[k] = take(4);
+        }
     }
     pl.total = off;
 }
@@ -849,7 +960,17 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     } else {
         net->d_ping = (float *)(base + pl.ping);
         net->d_pong = (float *)(base + pl.pong);
+        for (int k = 0; k < 2; ++k) {
+            net->d_flags[k] = (int32_t *)(base + pl.flags[k]);
+            net->d_map[k] = (int32_t *)(base + pl.map[k]);
+            net->d_n_live[k] = (int32_t *)(base + pl.n_live[k]);
+        }
     }
+    net->bias_nonpos = true;
+    for (int32_t l = 1; l < n_layers; ++l)
+        if (layers[l].bias)
+            for (int32_t r = 0; r < layers[l].n_out; ++r)
+                if (!(layers[l].bias[r] <= 0.0f)) net->bias_nonpos = false;
     *out = net;
     return SDNN_OK;
 }
@@ -892,9 +1013,12 @@ static int pick_v_spmm(int B, const void *a, const void *b, const void *c)
 // when a pass is run as two independent half-batches on two streams); force_v: samples per lane, 0 = choose.
 template <int MODE>
 static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float *out,
-                       const float *aux, int B, hipStream_t stream, int part = 0, int n_parts = 1, int force_v = 0)
+                       const float *aux, int B, hipStream_t stream, int part = 0, int n_parts = 1, int force_v = 0,
+                       const int32_t *n_live = nullptr, int32_t *flags = nullptr)
 {
     SpmmArgs a;
+    a.n_live = n_live;
+    a.flags = flags;
     if (MODE == 0) {
         a.row_ptr = d.row_ptr; a.idx = d.col_idx; a.perm = nullptr; a.sched = d.sched;
         a.n_rows = d.n_out;
@@ -1003,10 +1127,64 @@ extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *
     return SDNN_OK;
 }
 
+
 static unsigned ew_blocks(size_t n)
 {
     size_t b = (n + 255) / 256;
     return (unsigned)std::min<size_t>(std::max<size_t>(b, 1), 8192);
+}
+
+extern "C" int sdnn_forward_skip_dead(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL,
+                                      int32_t check_every, int32_t *d_n_live, void *stream_)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!d_X0 || !d_XL) return fail(net, SDNN_EINVAL, "d_X0 or d_XL is NULL");
+    if (B < 1 || B > net->cfg.max_batch)
+        return fail(net, SDNN_EINVAL, "B = %d outside 1..max_batch = %d", B, net->cfg.max_batch);
+    if (check_every < 1) return fail(net, SDNN_EINVAL, "check_every must be >= 1");
+    if (net->cfg.training) return fail(net, SDNN_ESTATE, "dead-sample skipping is for inference nets (training = 0)");
+    if (net->cfg.activation != SDNN_ACT_RELU_CAP)
+        return fail(net, SDNN_ESTATE, "dead-sample skipping needs the ReLU activation (f(0) = 0)");
+    if (!net->bias_nonpos)
+        return fail(net, SDNN_ESTATE, "dead-sample skipping needs every bias of layers 2..L to be <= 0 "
+                                      "(a positive bias revives a dead sample; replaced biases are not inspected)");
+    if (B > PACK_MAX_B) return fail(net, SDNN_EINVAL, "B = %d: dead-sample skipping packs blocks of at most %d samples", B, PACK_MAX_B);
+    hipStream_t stream = (hipStream_t)stream_;
+    net->state = ST_IDLE;
+    const int L = net->n_layers;
+    hipLaunchKernelGGL(k_skip_init, dim3(ew_blocks((size_t)B)), dim3(256), 0, stream, net->d_map[0], net->d_flags[0],
+                       net->d_flags[1], net->d_n_live[0], B);
+    HIP_TRY(net, hipGetLastError());
+    const float *in = d_X0;
+    int k = 0; // packing round: its state is in slot k & 1, the next round's in the other slot
+    for (int l = 0; l < L; ++l) {
+        const LayerDev &d = net->layers[l];
+        float *out = (l & 1) ? net->d_pong : net->d_ping;
+        // one sample: nothing to pack, this is the plain pass
+        const bool check = (l + 1) % check_every == 0 && l + 1 < L && B > 1 && d.n_out > 0;
+        const int rc = launch_spmm<0>(net, d, in, out, d.bias, B, stream, 0, 1, 0, net->d_n_live[k & 1],
+                                      check ? net->d_flags[k & 1] : nullptr);
+        if (rc) return rc;
+        if (check) {
+            hipLaunchKernelGGL(k_pack, dim3((unsigned)((d.n_out + PACK_ROWS - 1) / PACK_ROWS)), dim3(256), 0, stream, out,
+                               d.n_out, B, net->d_flags[k & 1], net->d_n_live[k & 1], net->d_map[k & 1],
+                               net->d_n_live[(k + 1) & 1], net->d_map[(k + 1) & 1], net->d_flags[(k + 1) & 1]);
+            HIP_TRY(net, hipGetLastError());
+            ++k;
+        }
+        in = out;
+    }
+    const int n_last = net->layers[L - 1].n_out;
+    if (n_last > 0) {
+        hipLaunchKernelGGL(k_fill_f32, dim3(ew_blocks((size_t)n_last * B)), dim3(256), 0, stream, d_XL,
+                           (size_t)n_last * B, 0.0f);
+        hipLaunchKernelGGL(k_scatter_cols, dim3((unsigned)((B + 255) / 256), (unsigned)((n_last + LIVE_ROWS - 1) / LIVE_ROWS)),
+                           dim3(256), 0, stream, in, d_XL, n_last, B, net->d_map[k & 1], net->d_n_live[k & 1]);
+        HIP_TRY(net, hipGetLastError());
+    }
+    if (d_n_live) HIP_TRY(net, hipMemcpyAsync(d_n_live, net->d_n_live[k & 1], 4, hipMemcpyDeviceToDevice, stream));
+    net->B = B;
+    return SDNN_OK;
 }
 
 extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
@@ -1163,7 +1341,10 @@ extern "C" int sdnn_set_weights(sdnn_net *net, int32_t layer, const float *d_val
     const LayerDev &d = net->layers[layer - 1];
     int rc = SDNN_OK;
     if (d_values) rc = copy_dd(net, d.vals, d_values, 4 * (size_t)d.nnz, stream_);
-    if (!rc && d_bias) rc = copy_dd(net, d.bias, d_bias, 4 * (size_t)d.n_out, stream_);
+    if (!rc && d_bias) {
+        rc = copy_dd(net, d.bias, d_bias, 4 * (size_t)d.n_out, stream_);
+        if (layer > 1) net->bias_nonpos = false; // device data: its signs are not inspected
+    }
     return rc;
 }
 

@@ -43,6 +43,7 @@ SIGNATURES = {
     "sdnn_create": (C.c_int, [C.POINTER(sdnn_layer), _I32, C.POINTER(sdnn_config), _P, _SZ, _P, C.POINTER(_P)]),
     "sdnn_destroy": (None, [_P]),
     "sdnn_forward": (C.c_int, [_P, _P, _I32, _P, _P]),
+    "sdnn_forward_skip_dead": (C.c_int, [_P, _P, _I32, _P, _I32, _P, _P]),
     "sdnn_backward": (C.c_int, [_P, _P, _P]),
     "sdnn_sgd_step": (C.c_int, [_P, C.c_float, _P]),
     "sdnn_get_activation": (C.c_int, [_P, _I32, _P, _P]),
@@ -190,6 +191,13 @@ class Net:
     def sdnn_forward(self, x0, xl=None, stream=None):
         b = x0.shape[1]
         _check(lib().sdnn_forward(self._handle, _dp(x0), b, _dp(xl), _stream_ptr(stream)), self._handle)
+        return xl
+
+    def sdnn_forward_skip_dead(self, x0, xl, check_every: int = 4, n_live=None, stream=None):
+        """n_live: None or an int32 device tensor of one element that receives the live-sample count."""
+        b = x0.shape[1]
+        _check(lib().sdnn_forward_skip_dead(self._handle, _dp(x0), b, _dp(xl), int(check_every), _dp(n_live),
+                                            _stream_ptr(stream)), self._handle)
         return xl
 
     def sdnn_backward(self, dloss, stream=None):

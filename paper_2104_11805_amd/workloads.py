@@ -21,7 +21,7 @@ Layout conventions used everywhere in this repository:
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import List, Optional
+from typing import List, Optional, Sequence
 
 import numpy as np
 
@@ -186,6 +186,14 @@ def ragged_layer(seed: int, n_out: int, n_in: int, density: float, n_long_rows: 
 def binary_inputs(seed: int, n: int, b: int, density: float) -> np.ndarray:
     rng = np.random.default_rng(seed)
     return (rng.random((n, b)) < density).astype(np.float32)
+
+
+def mixed_density_inputs(seed: int, n: int, b: int, densities: Sequence[float]) -> np.ndarray:
+    """Binary inputs [n][b] whose column s is Bernoulli(densities[s % len(densities)]): samples that die
+    at different depths next to samples that stay alive."""
+    rng = np.random.default_rng(seed)
+    dens = np.asarray([densities[s % len(densities)] for s in range(b)], dtype=np.float64)
+    return (rng.random((n, b)) < dens[None, :]).astype(np.float32)
 
 
 def normal_inputs(seed: int, n: int, b: int) -> np.ndarray:
