@@ -46,8 +46,8 @@ void FN(oracle_set_threads)(int n) { (void)n; }
 
 #include <math.h>
 
-/* Two activations (Section 4.1 names "ReLu, sigmoid etc."; the paper's training
- * experiments use the sigmoid, Section 6.1):
+/* Two activations (Section 4.1 leaves f open and lists ReLU and the sigmoid among the choices;
+ * the paper's training experiments use the sigmoid, Section 6.1):
  *   kind 0: f(z) = min(max(z, 0), cap); cap = +inf gives plain ReLU.  f' is 1
  *           strictly inside (0, cap) and 0 elsewhere, evaluated from the stored
  *           output x = f(z): 0 < x < cap  <=>  0 < z < cap.
