@@ -41,6 +41,10 @@
  * memory: the caller hands in one workspace at sdnn_create and keeps it alive
  * until sdnn_destroy.
  *
+ * The three passes allocate nothing and never synchronise, so a caller may
+ * capture them in a HIP graph.  A net is not thread-safe: calls on one net must
+ * not overlap (different nets are independent).
+ *
  * Every function that returns int returns SDNN_OK or a negative code and never
  * throws or aborts; sdnn_last_error gives the message of the last failure.
  */

@@ -293,3 +293,43 @@ def test_paper_training_setup_wide_net_two_steps():
             P.assert_grad_close(gb, b, f"step {s} layer {k + 1} bias")
             lay.values, lay.bias = v, b
     net.close()
+
+
+@pytest.mark.parametrize("b", [256, 64, 1])
+def test_training_step_captured_in_a_graph_replays_like_eager(b):
+    """The library allocates nothing and orders all work on the caller's stream (the helper stream
+    of the two-half-batch path is forked and joined with events), so a whole step can be captured
+    in a HIP graph.  Every replay is checked against an eager twin net, with eager work and
+    synchronisations between the replays; the oracle checks the first step."""
+    work = wl.make_config(1, n=512, n_layers=7, b_infer=b, b_train=b, density=0.4)
+    x0, y = P.dev(work.x_train), P.dev(work.targets)
+
+    def step(net, xl, dl):
+        net.sdnn_forward(x0, xl)
+        sdnn.sdnn_mse_dloss(xl, y, out=dl)
+        net.sdnn_backward(dl)
+        net.sdnn_sgd_step(work.lr)
+
+    eager = sdnn.Net(work.layers, work.act_cap, b, training=True)
+    graphed = sdnn.Net(work.layers, work.act_cap, b, training=True)
+    xe, de = torch.empty(512, b, device=P.DEV), torch.empty(512, b, device=P.DEV)
+    xg, dg = torch.empty_like(xe), torch.empty_like(xe)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):       # capture records, it does not run
+        step(graphed, xg, dg)
+    torch.cuda.synchronize()
+    for it in range(4):
+        graph.replay()
+        step(eager, xe, de)                           # eager work of the program between replays
+        torch.cuda.synchronize()
+        assert torch.equal(xg, xe), f"replay {it}: X_L differs from the eager step"
+        for k in (1, 4, 7):
+            for a, c in zip(graphed.sdnn_get_weights(k), eager.sdnn_get_weights(k)):
+                assert torch.equal(a, c), f"replay {it}: layer {k} differs from the eager step"
+        if it == 0:
+            o = P.oracle_train_step(work, work.x_train)
+            assert np.array_equal(P.host(xg), o["xs"][-1])
+            P.assert_grad_close(P.host(graphed.sdnn_get_weights(7)[0]), o["new"][6][0], "graph step weights")
+    eager.close(); graphed.close()
