@@ -84,7 +84,18 @@ typedef struct {
     int32_t training;    /* 1: keep X_0..X_L and Delta_1..Delta_L; 0: inference only */
     int32_t update_bias; /* 1: sdnn_sgd_step also updates the biases             */
     int32_t activation;  /* SDNN_ACT_RELU_CAP or SDNN_ACT_SIGMOID (act_cap ignored) */
+    int32_t fuse_gradient; /* SDNN_FUSE_AUTO / _ON / _OFF, see below               */
 } sdnn_config;
+
+/* Where the batch allows it (at most 64 samples per launch, short rows), sdnn_backward can form
+ * the gradient of the stored entries (Eq. 4) in the same sweep that back-propagates through W_l
+ * (Eq. 7): both need the rows of Delta_l that an entry points at.  sdnn_sgd_step is then a
+ * streaming pass.  Same results within the rounding of the sum over samples; costs 8 more bytes
+ * of workspace per stored entry.  AUTO turns it on for wide layers (mean n_out >= 32768), where
+ * it is faster. */
+#define SDNN_FUSE_AUTO 0
+#define SDNN_FUSE_ON 1
+#define SDNN_FUSE_OFF (-1)
 
 /* ---- setup (Algorithm 1's inputs {W^k}; the paper likewise precomputes its
  *      per-layer index maps once, outside the timed iterations) ------------- */

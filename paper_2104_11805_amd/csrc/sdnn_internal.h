@@ -25,4 +25,5 @@ struct LayerDev {
     float *X_prev;            // X_{l-1}  [n_in][B]   (training mode)
     float *X;                 // X_l      [n_out][B]  (training mode)
     float *D;                 // Delta_l  [n_out][B]  (training mode)
+    float *G[2];              // [nnz] each: gradient of the stored entries over one half of the batch (training mode)
 };

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libsdnn.so")
 
 SDNN_OK, SDNN_EINVAL, SDNN_ESTATE, SDNN_ENOMEM, SDNN_EHIP = 0, -1, -2, -3, -4
 SDNN_ACT_RELU_CAP, SDNN_ACT_SIGMOID = 0, 1
+SDNN_FUSE_AUTO, SDNN_FUSE_ON, SDNN_FUSE_OFF = 0, 1, -1
 
 
 class SdnnError(RuntimeError):
@@ -33,7 +34,7 @@ class sdnn_layer(C.Structure):
 
 class sdnn_config(C.Structure):
     _fields_ = [("act_cap", C.c_float), ("max_batch", C.c_int32), ("training", C.c_int32),
-                ("update_bias", C.c_int32), ("activation", C.c_int32)]
+                ("update_bias", C.c_int32), ("activation", C.c_int32), ("fuse_gradient", C.c_int32)]
 
 
 # name -> (restype, argtypes); every symbol include/sdnn.h declares
@@ -145,7 +146,8 @@ class Net:
     """Owns the workspace tensor and the opaque sdnn_net handle."""
 
     def __init__(self, layers: Sequence, act_cap: float, max_batch: int, training: bool = True,
-                 update_bias: bool = True, device: str = "cuda:0", activation: str = "relu"):
+                 update_bias: bool = True, device: str = "cuda:0", activation: str = "relu",
+                 fuse_gradient: int = 0):
         import torch
         self._handle = None
         self._keep = []
@@ -158,7 +160,8 @@ class Net:
                                 _hp(va).value if va.size else None,
                                 None if bi is None else _hp(bi).value)
         self.cfg = sdnn_config(float(act_cap), int(max_batch), int(training), int(update_bias),
-                               {"relu": SDNN_ACT_RELU_CAP, "sigmoid": SDNN_ACT_SIGMOID}[activation])
+                               {"relu": SDNN_ACT_RELU_CAP, "sigmoid": SDNN_ACT_SIGMOID}[activation],
+                               int(fuse_gradient))
         nbytes = C.c_size_t(0)
         _check(lib().sdnn_workspace_bytes(arr, len(layers), C.byref(self.cfg), C.byref(nbytes)))
         self.device = torch.device(device)

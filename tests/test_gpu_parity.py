@@ -333,3 +333,40 @@ def test_training_step_captured_in_a_graph_replays_like_eager(b):
             assert np.array_equal(P.host(xg), o["xs"][-1])
             P.assert_grad_close(P.host(graphed.sdnn_get_weights(7)[0]), o["new"][6][0], "graph step weights")
     eager.close(); graphed.close()
+
+
+@pytest.mark.parametrize("b", [5, 64, 128, 130])
+@pytest.mark.parametrize("activation", ["relu", "sigmoid"])
+def test_fused_backward_and_gradient(b, activation):
+    """SDNN_FUSE_ON: back-propagation and the gradient of the stored entries in one sweep (whole batch
+    for B <= 64, two half-batch launches for B = 128; B = 130 cannot be fused and takes the separate
+    update), then the streaming descent step.  Uneven rows, several 16-entry groups per row, empty rows."""
+    work = wl.tiny_net(81, sizes=(150, 90, 200, 60, 110), density=0.25, b=b)
+    work.activation = activation
+    lens = np.concatenate([np.diff(l.row_ptr) for l in work.layers])
+    assert lens.max() > 40 and lens.min() < 16
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05, fuse_gradient=sdnn.SDNN_FUSE_ON)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05)
+    st = P.compare_step(g, o, f"fused b={b} {activation}", exact_fwd=(activation == "relu"))
+    assert st["live_g"] == 4 and st["live_d"] == 4
+    plain = P.gpu_train_step(work, work.x_infer, lr=0.05, fuse_gradient=sdnn.SDNN_FUSE_OFF)
+    for k in range(1, 5):
+        assert np.array_equal(g["deltas"][k], plain["deltas"][k]), "the fused sweep must back-propagate the same bits"
+    for (v, bias), (pv, pb) in zip(g["new"], plain["new"]):
+        P.assert_grad_close(v, pv, "fused vs separate update")     # two fp32 partial sums instead of one
+        assert np.array_equal(bias, pb)
+
+
+def test_fused_gradient_options_and_empty_layer():
+    """Fused path with update_bias off, a layer without entries, and lr = 0 (weights bit-identical)."""
+    work = wl.tiny_net(82, sizes=(30, 50, 40, 20), density=0.2, b=33)
+    mid = work.layers[1]
+    mid.row_ptr = np.zeros_like(mid.row_ptr); mid.col_idx = mid.col_idx[:0]; mid.values = mid.values[:0]
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05, update_bias=False, fuse_gradient=sdnn.SDNN_FUSE_ON)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05, update_bias=False)
+    P.compare_step(g, o, "fused no-bias")
+    for lay, (v, bias) in zip(work.layers, g["new"]):
+        assert np.array_equal(bias, lay.bias)
+    z = P.gpu_train_step(work, work.x_infer, lr=0.0, fuse_gradient=sdnn.SDNN_FUSE_ON)
+    for lay, (v, bias) in zip(work.layers, z["new"]):
+        assert np.array_equal(v, lay.values) and np.array_equal(bias, lay.bias)
