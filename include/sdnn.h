@@ -91,7 +91,7 @@ typedef struct {
  * the gradient of the stored entries (Eq. 4) in the same sweep that back-propagates through W_l
  * (Eq. 7): both need the rows of Delta_l that an entry points at.  sdnn_sgd_step is then a
  * streaming pass.  Same results within the rounding of the sum over samples; costs 8 more bytes
- * of workspace per stored entry.  AUTO turns it on for wide layers (mean n_out >= 32768), where
+ * of workspace per stored entry.  AUTO turns it on for wide layers (mean n_out >= 16384), where
  * it is faster. */
 #define SDNN_FUSE_AUTO 0
 #define SDNN_FUSE_ON 1

@@ -702,7 +702,7 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
 // K4b: the descent step when the fused backward kernels have left the gradient of the stored
 // entries in G[0] (and G[1], the other half of the batch): vals -= lr * g, a flat streaming pass
 // over the entries of every layer (grid = (chunks of entries, layers)); k_apply_bias forms the bias
-// gradient sum_s Delta(row, s), a wavefront per row.
+// gradient sum_s Delta(row, s).
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_apply(const LayerDev *__restrict__ layers, int n_parts, float lr)
 {
@@ -718,18 +718,31 @@ __global__ void __launch_bounds__(256) k_apply(const LayerDev *__restrict__ laye
     }
 }
 
+// 16 lanes per row, four rows per wavefront at a time, 16 consecutive rows per wavefront.
 __global__ void __launch_bounds__(BLOCK_THREADS) k_apply_bias(const LayerDev *__restrict__ layers, int B, float lr)
 {
     const LayerDev &L = layers[blockIdx.y];
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
-    if (row >= L.n_out) return;
-    const float *drow = L.D + (size_t)row * B;
-    double sum = 0.0;
-    for (int s = lane; s < B; s += 64) sum += (double)drow[s];
+    const int lane = threadIdx.x & 63, l = lane & 15;
+    const int row0 = (blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6)) * 16 + (lane >> 4);
+    const bool vec = (B & 3) == 0; // rows of Delta are 16-byte aligned
+    for (int k = 0; k < 4; ++k) {
+        const int row = row0 + 4 * k;
+        double sum = 0.0;
+        if (row < L.n_out) {
+            const float *drow = L.D + (size_t)row * B;
+            if (vec) {
+                for (int s = 4 * l; s < B; s += 64) {
+                    const float4 d = *reinterpret_cast<const float4 *>(drow + s);
+                    sum += (double)d.x; sum += (double)d.y; sum += (double)d.z; sum += (double)d.w;
+                }
+            } else {
+                for (int s = l; s < B; s += 16) sum += (double)drow[s];
+            }
+        }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    if (lane == 0) L.bias[row] = (float)((double)L.bias[row] - (double)lr * (double)(float)sum);
+        for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+        if (l == 0 && row < L.n_out) L.bias[row] = (float)((double)L.bias[row] - (double)lr * (double)(float)sum);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -947,14 +960,14 @@ static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_c
 
 // The fused backward + gradient kernels pay on wide layers, whose launches are bound by gather
 // throughput; on narrow ones, bound by the latency of a launch, the separate update is faster
-// (measured: 4096 rows -6 %, 16384 rows even, 65536 rows +10 %).
+// (measured step time: 4096 rows +5 %, 16384 rows -2 %, 65536 rows -16 %).
 static bool grad_buffers_wanted(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg)
 {
     if (!cfg->training || cfg->fuse_gradient == SDNN_FUSE_OFF) return false;
     if (cfg->fuse_gradient == SDNN_FUSE_ON) return true;
     int64_t rows = 0;
     for (int32_t l = 0; l < n_layers; ++l) rows += layers[l].n_out;
-    return rows >= (int64_t)32768 * n_layers;
+    return rows >= (int64_t)16384 * n_layers;
 }
 
 static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg, Plan &pl)
@@ -1518,7 +1531,7 @@ extern "C" int sdnn_sgd_step(sdnn_net *net, float lr, void *stream_)
                 hipLaunchKernelGGL(k_apply, dim3((unsigned)std::min(4096, (max_nnz + 2047) / 2048), (unsigned)nl), dim3(256), 0,
                                    (hipStream_t)stream_, net->d_layers + l0, net->grad_parts, lr);
             if (max_rows > 0 && net->cfg.update_bias)
-                hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((max_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), (unsigned)nl),
+                hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((max_rows + 16 * WAVES_PER_BLOCK - 1) / (16 * WAVES_PER_BLOCK)), (unsigned)nl),
                                    dim3(BLOCK_THREADS), 0, (hipStream_t)stream_, net->d_layers + l0, net->B, lr);
             HIP_TRY(net, hipGetLastError());
         }

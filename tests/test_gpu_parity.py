@@ -354,7 +354,7 @@ def test_fused_backward_and_gradient(b, activation):
         assert np.array_equal(g["deltas"][k], plain["deltas"][k]), "the fused sweep must back-propagate the same bits"
     for (v, bias), (pv, pb) in zip(g["new"], plain["new"]):
         P.assert_grad_close(v, pv, "fused vs separate update")     # two fp32 partial sums instead of one
-        assert np.array_equal(bias, pb)
+        P.assert_grad_close(bias, pb, "fused vs separate bias update")
 
 
 def test_fused_gradient_options_and_empty_layer():
