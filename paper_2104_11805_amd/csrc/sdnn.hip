@@ -1191,7 +1191,6 @@ static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a 
 // and the alignment of the operands allow without idling most of the wave.
 static int pick_v_spmm(int B, const void *a, const void *b, const void *c)
 {
-
     if (B % 4 == 0 && B > 128 && aligned(a, 16) && aligned(b, 16) && aligned(c, 16)) return 4;
     if (B % 2 == 0 && B > 64 && aligned(a, 8) && aligned(b, 8) && aligned(c, 8)) return 2;
     return 1;
