@@ -179,3 +179,18 @@ def test_host_setup_routines_under_sanitizers(tmp_path):
     out = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
     assert out.returncode == 0, out.stdout + out.stderr
     assert "host setup: ok" in out.stdout
+
+
+def test_header_is_plain_c_and_host_entry_points_link(tmp_path):
+    """include/sdnn.h compiled as C99 (-pedantic -Werror) into a program that links libsdnn.so and calls
+    the host-only entry points."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sdnn.lib()                                      # makes sure the library is built
+    exe = str(tmp_path / "c_abi_check")
+    libdir = os.path.dirname(sdnn.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c_abi_check.c"), "-o", exe, "-L", libdir, "-lsdnn",
+                    "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
+    assert "c abi ok" in out
