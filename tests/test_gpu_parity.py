@@ -370,3 +370,24 @@ def test_fused_gradient_options_and_empty_layer():
     z = P.gpu_train_step(work, work.x_infer, lr=0.0, fuse_gradient=sdnn.SDNN_FUSE_ON)
     for lay, (v, bias) in zip(work.layers, z["new"]):
         assert np.array_equal(v, lay.values) and np.array_equal(bias, lay.bias)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_small_nets(seed):
+    """A seeded sweep over shapes, densities, batch sizes, activations, caps and the gradient-fusion
+    switch: every pass of every case against the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    depth = int(rng.integers(1, 5))
+    sizes = tuple(int(x) for x in rng.integers(1, 260, size=depth + 1))
+    density = float(rng.choice([0.02, 0.1, 0.3, 0.7, 1.0]))
+    b = int(rng.choice([1, 2, 3, 17, 63, 64, 65, 100, 128, 129, 192, 256]))
+    activation = str(rng.choice(["relu", "sigmoid"]))
+    cap = float(rng.choice([np.inf, 1.5])) if activation == "relu" else float("inf")
+    fuse = int(rng.choice([sdnn.SDNN_FUSE_AUTO, sdnn.SDNN_FUSE_ON, sdnn.SDNN_FUSE_OFF]))
+    update_bias = bool(rng.integers(0, 2))
+    work = wl.tiny_net(300 + seed, sizes=sizes, density=density, b=b, cap=cap, scale=float(rng.choice([0.3, 1.0])))
+    work.activation = activation
+    what = f"seed {seed}: sizes {sizes} density {density} b {b} {activation} cap {cap} fuse {fuse} bias {update_bias}"
+    g = P.gpu_train_step(work, work.x_infer, lr=0.05, update_bias=update_bias, fuse_gradient=fuse)
+    o = P.oracle_train_step(work, work.x_infer, lr=0.05, update_bias=update_bias)
+    P.compare_step(g, o, what, exact_fwd=(activation == "relu"))
