@@ -103,3 +103,43 @@ def test_skip_dead_refuses_nets_where_dead_samples_can_revive():
     assert e.value.code == sdnn.SDNN_EINVAL
     net.sdnn_set_weights(2, None, P.dev(work.layers[1].bias))
     refused(net, "bias")
+
+
+def test_skip_dead_block_size_limits():
+    """The packing kernel holds one position per sample in LDS: 8192 samples work, more are refused."""
+    work = wl.tiny_net(73, sizes=(24, 40, 16), density=0.3, b=8192)
+    for l in work.layers:
+        l.bias = -np.abs(l.bias)
+    work.x_infer[:, 5::7] = 0.0
+    ref = P.O32.forward(work.layers, work.x_infer, work.act_cap)[-1]
+    net = sdnn.Net(work.layers, work.act_cap, 9000, training=False)
+    out = torch.empty(16, 8192, device=P.DEV)
+    n_live = torch.zeros(1, dtype=torch.int32, device=P.DEV)
+    net.sdnn_forward_skip_dead(P.dev(work.x_infer), out, check_every=1, n_live=n_live)
+    assert np.array_equal(P.host(out), ref)
+    assert 0 < int(n_live.item()) <= 8192 - len(range(5, 8192, 7))
+    big = torch.zeros(24, 9000, device=P.DEV)
+    with pytest.raises(sdnn.SdnnError) as e:
+        net.sdnn_forward_skip_dead(big, torch.empty(16, 9000, device=P.DEV))
+    assert e.value.code == sdnn.SDNN_EINVAL and "8192" in str(e.value)
+    net.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_skip_dead_seeded_random_nets(seed):
+    rng = np.random.default_rng(9500 + seed)
+    depth = int(rng.integers(2, 7))
+    sizes = tuple(int(x) for x in rng.integers(1, 200, size=depth + 1))
+    b = int(rng.choice([2, 31, 64, 65, 255, 256, 300, 1024]))
+    k = int(rng.choice([1, 2, 3, 5]))
+    work = wl.tiny_net(400 + seed, sizes=sizes, density=float(rng.choice([0.05, 0.2, 0.6])), b=b,
+                       cap=float(rng.choice([np.inf, 2.0])))
+    for l in work.layers:
+        l.bias = -np.abs(l.bias) * float(rng.choice([0.0, 1.0, 4.0]))     # larger negative biases kill more samples
+    work.x_infer[:, rng.random(b) < 0.3] = 0.0
+    ref = P.O32.forward(work.layers, work.x_infer, work.act_cap)[-1]
+    net = sdnn.Net(work.layers, work.act_cap, b, training=False)
+    out = torch.full((sizes[-1], b), -1.0, device=P.DEV)
+    net.sdnn_forward_skip_dead(P.dev(work.x_infer), out, check_every=k)
+    assert np.array_equal(P.host(out), ref), f"seed {seed}: sizes {sizes} b {b} every {k}"
+    net.close()
