@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check-every", type=int, default=4,
                     help="layers between two packings of the live samples in the skip-dead inference figure")
+    ap.add_argument("--infer-block", type=int, default=0,
+                    help="samples per sdnn_forward call of the inference figure (0: all, 1024 for N >= 65536)")
     ap.add_argument("--no-inference", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -148,7 +150,7 @@ def main():
     # ---- inference forward over the full sample set ----------------------
     infer = None
     if not args.no_inference:
-        block = min(Bi, 1024 if N >= 65536 else Bi)
+        block = args.infer_block or min(Bi, 1024 if N >= 65536 else Bi)
         inet = sdnn.Net(work.layers, work.act_cap, block, training=False)
         xi = to_dev(work.x_infer)
         blocks = [(s, min(block, Bi - s)) for s in range(0, Bi, block)]
