@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--infer-block", type=int, default=0,
                     help="samples per sdnn_forward call of the inference figure (0: all, 1024 for N >= 65536)")
     ap.add_argument("--no-inference", action="store_true")
+    ap.add_argument("--no-skip-dead", action="store_true", help="leave out the skip-dead inference figure")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -176,7 +177,7 @@ def main():
                  "hbm_frac": round(ibytes / (ims * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         # second figure, never the headline: the same inference with dead samples dropped (ReLU, biases <= 0);
         # the edge count in the numerator then includes edges that were never visited
-        if work.activation == "relu" and all((l.bias <= 0).all() for l in work.layers[1:]):
+        if not args.no_skip_dead and work.activation == "relu" and all((l.bias <= 0).all() for l in work.layers[1:]):
             n_live = torch.zeros(1, dtype=torch.int32, device=dev)
             xchk = [torch.empty_like(o) for o in xout]
 
