@@ -282,7 +282,7 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
 // "virtual blocks" blockIdx.x, blockIdx.x + gridDim.x, ...: a wavefront that
 // handles one short row and exits costs more to dispatch than to run.
 // gridDim.x is a multiple of 8, so a workgroup keeps its XCD's tiles.
-template <int V, int MODE, int U>
+template <int V, int MODE, int U, bool TILES_INNER = false>
 __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
 {
     const int lane = threadIdx.x & 63;
@@ -291,6 +291,19 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
     if (a.n_live) { // only the batch tiles that hold live columns
         n_tiles = min(n_tiles, ((unsigned)*a.n_live + 64u * V - 1u) / (64u * V));
         n_vblocks = n_tiles * a.n_rg;
+    }
+    if constexpr (TILES_INNER) {
+        // a few batch tiles shared by all XCDs: a wavefront keeps its row and walks the tiles, so the row's
+        // task record and entries are fetched once, and the whole chip gathers from one tile's slab at a time
+        for (unsigned rg = blockIdx.x; rg < a.n_rg; rg += gridDim.x) {
+            const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
+            if (r >= a.n_rows) continue;
+            const RowMeta m = load_meta<MODE>(a.sched, a.idx, a.vals, a.perm, r, lane);
+            for (unsigned tile = 0; tile < n_tiles; ++tile)
+                spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act,
+                                     tile + a.tile_base, lane, a.flags);
+        }
+        return;
     }
     for (unsigned vb = blockIdx.x; vb < n_vblocks; vb += gridDim.x) {
         unsigned tile, rg;
@@ -888,7 +901,7 @@ struct sdnn_net {
     float *d_x0 = nullptr;        // training: X_0 [n_in(1)][max_batch]
     float *d_ping = nullptr, *d_pong = nullptr; // inference: two activation buffers
     int n_cu = 0;                 // compute units of the device
-    int occ_spmm[2][3] = {{0, 0, 0}, {0, 0, 0}}; // resident workgroups per CU of k_spmm<V,MODE>
+    int occ_spmm[2][3][2] = {}; // resident workgroups per CU of k_spmm<V,MODE,8,tiles inner>
     int occ_grad = 0;             // the same for k_bwd_grad
     int grad_parts = 0;           // > 0: the last backward pass left the entries' gradient in G[0..grad_parts)
     hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
@@ -1208,6 +1221,7 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     SpmmArgs a;
     a.n_live = n_live;
     a.flags = flags;
+    a.g_part = nullptr; a.store_out = 1;
     if (MODE == 0) {
         a.row_ptr = d.row_ptr; a.idx = d.col_idx; a.perm = nullptr; a.sched = d.sched;
         a.n_rows = d.n_out;
@@ -1256,13 +1270,20 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
         fn = V == 4 ? (const void *)k_spmm<4, MODE, 8> : V == 2 ? (const void *)k_spmm<2, MODE, 8>
                                                                 : (const void *)k_spmm<1, MODE, 8>;
     uint64_t g = blocks;
+    // short rows and a few batch tiles (shared by all XCDs): workgroups are dealt row groups and walk the tiles
+    const bool tiles_inner = !long_rows && a.n_tiles >= 2 && a.n_tiles < 8;
+    if (tiles_inner) {
+        g = a.n_rg;
+        fn = V == 4 ? (const void *)k_spmm<4, MODE, 8, true> : V == 2 ? (const void *)k_spmm<2, MODE, 8, true>
+                                                                      : (const void *)k_spmm<1, MODE, 8, true>;
+    }
     if (!long_rows) {
-        int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0];
+        int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0][tiles_inner ? 1 : 0];
         if (per_cu == 0) {
             HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BLOCK_THREADS, 0));
             if (per_cu < 1) per_cu = 1;
         }
-        g = std::min(blocks, (uint64_t)per_cu * (uint64_t)net->n_cu);
+        g = std::min(g, (uint64_t)per_cu * (uint64_t)net->n_cu);
     }
     if (g >= 8) g &= ~(uint64_t)7; // keeps virtual block id % 8 == workgroup id % 8 (XCD-wise tiles)
     void *args[] = {(void *)&a};

@@ -391,3 +391,31 @@ def test_seeded_random_small_nets(seed):
     g = P.gpu_train_step(work, work.x_infer, lr=0.05, update_bias=update_bias, fuse_gradient=fuse)
     o = P.oracle_train_step(work, work.x_infer, lr=0.05, update_bias=update_bias)
     P.compare_step(g, o, what, exact_fwd=(activation == "relu"))
+
+
+@pytest.mark.parametrize("n,d,b,training", [(1000, 24, 2900, False), (1500, 8, 701, False), (2048, 40, 1026, True),
+                                             (777, 16, 4096, False), (1000, 24, 1024, False), (515, 16, 300, True),
+                                             (1030, 32, 390, False)])
+def test_uniform_rows_wide_batches(n, d, b, training):
+    """Layers whose rows all hold d entries, batches of several tiles: 2 to 7 tiles (a wavefront keeps
+    its row and walks the tiles) and 8 and more (tiles dealt to the XCDs); row counts that are no
+    multiple of the rows per workgroup, ragged last tile, 1, 2 and 4 samples per lane; mixed-sign
+    weights and biases."""
+    rng = np.random.default_rng(n + d)
+    layers = []
+    for l in range(3):
+        lay = wl.regular_layer(6000 + 10 * n + l, n, d, 1.0, 0.0)
+        lay.values = (rng.standard_normal(lay.values.size) / np.sqrt(d)).astype(np.float32)
+        lay.bias = (0.2 * rng.standard_normal(n)).astype(np.float32)
+        layers.append(lay)
+    x = wl.normal_inputs(6900 + n, n, b)
+    ref = P.O32.forward(layers, x, 1.0)
+    assert (ref[-1] > 0).any() and (ref[-1] == 0).any() and (ref[1] == 1.0).any()
+    net = sdnn.Net(layers, 1.0, b, training=training)
+    out = torch.empty(n, b, device=P.DEV)
+    net.sdnn_forward(P.dev(x), out)
+    assert np.array_equal(P.host(out), ref[-1])
+    if training:
+        for k in (1, 2):
+            assert np.array_equal(P.host(net.sdnn_get_activation(k, b)), ref[k])
+    net.close()
