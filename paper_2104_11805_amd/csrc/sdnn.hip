@@ -13,6 +13,13 @@
 //     needed per 8 edges before the weight is rewritten in place.
 //   * W^T is never stored: the transposed index lists, per column, the source
 //     rows and the positions of the values in the CSR array.
+//   * wide layers: the backward sweep also forms the gradient of the stored
+//     entries (k_bwd_grad, gathered rows parked in LDS), the descent step is
+//     then a streaming pass (k_apply).
+//   * one sample per step (B = 1): lanes over entries / rows instead of samples
+//     (k_spmv_stage, k_spmv_wave, k_spmv, k_update_b1).
+//   * inference that drops dead samples: flags set by the forward epilogue,
+//     in-place packing on the device (k_pack), no host synchronisation.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -30,7 +37,7 @@
 // ---------------------------------------------------------------------------
 
 #define WAVES_PER_BLOCK 4 // product kernels: 4 rows per workgroup (measured best of 1, 2, 4, 8)
-#define UPD_WAVES 1       // update kernel: one row per workgroup (measured best of 1, 2, 4, 8)
+#define UPD_WAVES 1       // update kernel: one wavefront per workgroup (measured best of 1, 2, 4, 8)
 #define BLOCK_THREADS (64 * WAVES_PER_BLOCK)
 
 template <int V> __device__ __forceinline__ void ldv(const float *p, float (&x)[V]);
