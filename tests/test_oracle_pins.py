@@ -348,3 +348,28 @@ def test_sigmoid_gradients_by_finite_differences():
                 worst = max(worst, abs((jp - jm) / (2 * h) - g[p]))
                 assert g[p] != 0
     assert worst <= 1e-8 * max(scale, 1e-3), worst      # smooth activation: O(h^2) error only
+
+
+def test_oracle_results_do_not_depend_on_the_thread_count():
+    """The OpenMP loops split independent outputs only: one thread and all threads give the same bits
+    in every pass (this is what lets the timing leg change the thread count)."""
+    from oracle.sdnn_oracle import Oracle, mse_dloss
+    work = wl.tiny_net(97, sizes=(60, 90, 70, 40), density=0.2, b=37)
+    orc = Oracle(np.float32)
+    n_all = orc.threads()
+    dfn = lambda x: mse_dloss(x, work.targets)
+    try:
+        orc.set_threads(1)
+        one = orc.train_step(work.layers, work.x_infer, work.act_cap, dfn, 0.05)
+        orc.set_threads(max(2, n_all))
+        many = orc.train_step(work.layers, work.x_infer, work.act_cap, dfn, 0.05)
+    finally:
+        orc.set_threads(n_all)
+    for a, c in zip(one[0], many[0]):
+        assert np.array_equal(a, c)
+    for a, c in zip(one[1][1:], many[1][1:]):
+        assert np.array_equal(a, c)
+    for (ga, gba), (gc, gbc) in zip(one[2], many[2]):
+        assert np.array_equal(ga, gc) and np.array_equal(gba, gbc)
+    for (va, ba), (vc, bc) in zip(one[3], many[3]):
+        assert np.array_equal(va, vc) and np.array_equal(ba, bc)
