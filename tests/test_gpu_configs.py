@@ -85,3 +85,25 @@ def test_config5_irregular_full_width():
     st = _train(work, work.x_train, "cfg5 x4096", scale=4096.0, live_layers=3)
     got, ref = _infer_columns(work, 2048, _sample_cols(2048, 5))
     assert 0.3 < (ref > 0).mean() < 0.7
+
+
+def test_config2_skip_dead_at_full_width():
+    """Config 2's net (first 60 layers) at its inference batch of 1024 with inputs of mixed density,
+    so that samples die at different depths: dropping them gives the bits of the plain pass, which
+    the oracle confirms on sampled columns."""
+    work = wl.make_config(2, n_layers=60)
+    work.x_infer = wl.mixed_density_inputs(2950, 4096, 1024, (0.05, 0.25, 0.30, 0.33, 0.36, 0.45))
+    net = sdnn.Net(work.layers, work.act_cap, 1024, training=False)
+    x = P.dev(work.x_infer)
+    plain = torch.empty(4096, 1024, device=P.DEV)
+    skipped = torch.full((4096, 1024), -1.0, device=P.DEV)
+    n_live = torch.zeros(1, dtype=torch.int32, device=P.DEV)
+    net.sdnn_forward(x, plain)
+    net.sdnn_forward_skip_dead(x, skipped, check_every=4, n_live=n_live)
+    assert torch.equal(plain, skipped)
+    cols = np.r_[0:12, 500:512, 1012:1024]
+    ref = P.O32.forward(work.layers, work.x_infer[:, cols], work.act_cap)
+    P.assert_forward_close(P.host(skipped)[:, cols], ref[-1], "skip-dead inference")
+    alive = int((P.host(plain) != 0).any(axis=0).sum())
+    assert 0 < alive < 1024 and alive <= int(n_live.item()) < 1024
+    net.close()
