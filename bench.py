@@ -7,6 +7,12 @@ is edges/s = (sum of nnz over the layers) x samples / seconds, the throughput
 definition of the paper's inference table (Section 6.4), applied to the full
 training step and, in a second figure, to the inference forward pass.
 
+The default workload is the largest configuration at full depth (config 4:
+65536 neurons per layer, 120 layers, 251 M stored entries, minibatch 64,
+8192 inference samples streamed in blocks of 1024).  The other four
+configurations are measured in the same run, each at full depth, and carried in
+the key "other_configs" of the same JSON line.
+
 Prints ONE JSON line.  Inputs are resident in HBM before the timed region.
 """
 import argparse
@@ -20,61 +26,73 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+T_START = time.time()
+
+# input density just above the point where the benchmark nets die (-bias): every activation stays non-zero
+LIVE_DENSITY = {1: 0.40, 2: 0.40, 3: 0.40, 4: 0.60}
 
 
-def layer_bytes(n, nnz, b):
-    """Algorithmic HBM bytes of one launch per layer (each array moved once)."""
+def log(msg):
+    print(f"[bench {time.time() - T_START:6.1f}s] {msg}", file=sys.stderr, flush=True)
+
+
+def layer_bytes(n, nnz, b, fused):
+    """Algorithmic HBM bytes per layer of each pass (every array moved once; gathers served on chip).
+
+    forward   index + values (8 nnz), row schedule (16 n), bias (4 n), X in and X out
+    backward  transposed index + position (8 nnz), values through it (4 nnz), schedule, Delta in, X mask, Delta out;
+              the fused sweep also writes the gradient of the stored entries (4 nnz)
+    update    separate: index (4 nnz), values read + written (8 nnz), schedule, bias r/w, Delta, X
+              after a fused sweep: values r/w + gradient read (12 nnz), bias r/w, Delta (bias gradient)
+    """
     act = 4 * n * b
-    fwd = 8 * nnz + 4 * (n + 1) + 4 * n + 2 * act                 # W, row_ptr, bias, X in, X out
-    bwd = 12 * nnz + 4 * (n + 1) + 3 * act                          # index+perm, values, D in, X mask, D out
-    upd = 8 * nnz + 4 * nnz + 4 * (n + 1) + 8 * n + 2 * act         # W r/w, bias r/w, D, X
+    fwd = 8 * nnz + 16 * n + 4 * n + 2 * act
+    bwd = 12 * nnz + 16 * n + 3 * act + (4 * nnz if fused else 0)
+    upd = (12 * nnz + 8 * n + act) if fused else (12 * nnz + 16 * n + 8 * n + 2 * act)
     return fwd, bwd, upd
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
-    ap.add_argument("--layers", type=int, default=None, help="depth prefix (default: full depth)")
-    ap.add_argument("--density", type=float, default=None, help="input density override (live inputs)")
-    ap.add_argument("--paper-setup", action="store_true",
-                    help="the paper's own training experiment: sigmoid, weights U[-1,1], one input vector per step")
-    ap.add_argument("--n", type=int, default=1024, help="neurons per layer for --paper-setup")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--check-every", type=int, default=4,
-                    help="layers between two packings of the live samples in the skip-dead inference figure")
-    ap.add_argument("--infer-block", type=int, default=0,
-                    help="samples per sdnn_forward call of the inference figure (0: all, 1024 for N >= 65536)")
-    ap.add_argument("--no-inference", action="store_true")
-    ap.add_argument("--no-skip-dead", action="store_true", help="leave out the skip-dead inference figure")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def workload_name(cfg, n, n_layers):
+    return (f"config {cfg}: N={n}, L={n_layers}, 32 nnz/row" if cfg < 5
+            else f"config 5: N={n}, L={n_layers}, heavy-tailed rows")
 
+
+def run_config(cfg, args, steps, warmup, headline):
+    """Training step and inference of one configuration; returns the figures as a dict."""
     import numpy as np
     import torch
     from paper_2104_11805_amd import sdnn, workloads as wl
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    if args.paper_setup:
-        return paper_setup_bench(args, np, torch, sdnn, wl)
+    layers_arg = args.layers if headline else None
+    density_arg = args.density if headline else None
     t0 = time.time()
-    work = wl.make_config(args.config, n_layers=args.layers, density=args.density)
+    work = wl.make_config(cfg, n_layers=layers_arg, density=density_arg)
     N, L, nnz_total = work.n, len(work.layers), work.total_nnz
     Bt, Bi = work.train_batch, work.x_infer.shape[1]
     gen_s = time.time() - t0
+    log(f"config {cfg}: generated {L} layers, {nnz_total} entries, inputs {work.x_infer.shape} in {gen_s:.1f} s")
 
     def to_dev(a, dtype=None):
         t = torch.from_numpy(np.ascontiguousarray(a))
         return (t.to(dtype) if dtype is not None else t).to(dev)
 
     # ---- training step --------------------------------------------------
+    t0 = time.time()
     net = sdnn.Net(work.layers, work.act_cap, Bt, training=True)
+    torch.cuda.synchronize()
+    create_s = time.time() - t0
+    log(f"config {cfg}: training net created in {create_s:.1f} s, workspace {net.workspace_bytes / 2**30:.2f} GiB")
+    # which kernels the library picks for this shape (its measured launch policy, restated here to name them):
+    # short rows and small layers run as two half-batches on two streams; wide layers (>= 16384 rows) with launches
+    # of at most 64 samples form the gradient in the backward sweep
+    short_rows = nnz_total < 128 * N * L
+    split = short_rows and Bt % 128 == 0 and N * Bt <= 2 ** 21
+    fused = short_rows and N >= 16384 and ((split and Bt == 128) or (not split and 1 < Bt <= 64))
+    if split:
+        v = 4 if Bt % 512 == 0 else 2 if Bt % 256 == 0 else 1
+    else:
+        v = 4 if (Bt % 4 == 0 and Bt > 128) else 2 if (Bt % 2 == 0 and Bt > 64) else 1
     x0 = to_dev(work.x_train)
     xl = torch.empty(work.layers[-1].n_out, Bt, device=dev)
     dl = torch.empty_like(xl)
@@ -86,147 +104,184 @@ def main():
         loss_grad = lambda: sdnn.sdnn_softmax_ce_dloss(xl, lab, work.n_classes, out=dl)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    marks = []
 
-    def step(record=False):
-        e = [ev() for _ in range(4)] if record else None
-        if record: e[0].record()
-        net.sdnn_forward(x0, xl)
-        if record: e[1].record()
+    def step(x, marks=None):
+        e = [ev() for _ in range(4)] if marks is not None else None
+        if e: e[0].record()
+        net.sdnn_forward(x, xl)
+        if e: e[1].record()
         loss_grad()
         net.sdnn_backward(dl)
-        if record: e[2].record()
+        if e: e[2].record()
         net.sdnn_sgd_step(work.lr)
-        if record: e[3].record()
-        if record: marks.append(e)
+        if e: e[3].record()
+        if e: marks.append(e)
 
-    for _ in range(args.warmup):
-        step()
+    w_first = [t.clone() for t in net.sdnn_get_weights(1)]
+    w_last = [t.clone() for t in net.sdnn_get_weights(L)]
+    for _ in range(warmup):
+        step(x0)
+    marks = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(record=True)
+    for _ in range(steps):
+        step(x0, marks)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_step = wall * 1e3 / args.steps
+    ms_step = wall * 1e3 / steps
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in marks) / len(marks)
     bwd_ms = sum(e[1].elapsed_time(e[2]) for e in marks) / len(marks)
     upd_ms = sum(e[2].elapsed_time(e[3]) for e in marks) / len(marks)
     per_step = sorted(e[0].elapsed_time(e[3]) for e in marks)       # event time of each single step
     train_eps = nnz_total * Bt / (ms_step * 1e-3)
+    # did the timed steps change the weights?  (nominal inputs of configs 1-4: every gradient is exactly zero,
+    # so every timed step saw the same weights; otherwise the steps are a real descent)
+    unchanged = all(torch.equal(a, b) for a, b in zip(w_first + w_last,
+                                                      list(net.sdnn_get_weights(1)) + list(net.sdnn_get_weights(L))))
     # share of non-zero activations after layers 1, 2 and L of the minibatch (the nominal inputs of configs 1-4
     # die out after the first layers; the kernels never skip zeros, so the timing does not profit from it)
     net.sdnn_forward(x0, xl)
     active = {f"layer_{k}": round(float((net.sdnn_get_activation(k, Bt) != 0).float().mean()), 4)
               for k in sorted({1, min(2, L), L})}
+    log(f"config {cfg}: step {ms_step:.3f} ms (fwd {fwd_ms:.3f} bwd {bwd_ms:.3f} upd {upd_ms:.3f}), "
+        f"{train_eps:.3e} edges/s")
+
+    # ---- the same step on live inputs: every rep starts from the same weights, restored outside the events ----
+    live = None
+    if cfg in LIVE_DENSITY and density_arg is None and not args.no_live:
+        d_live = LIVE_DENSITY[cfg]
+        xlive = to_dev(wl.binary_inputs(1000 * cfg + 902, N, Bt, d_live))
+        saved = [tuple(t.clone() for t in net.sdnn_get_weights(k)) for k in range(1, L + 1)]
+        reps = max(3, steps // 4)
+        lmarks = []
+        for r in range(reps + 1):
+            for k in range(1, L + 1):
+                net.sdnn_set_weights(k, saved[k - 1][0], saved[k - 1][1])
+            step(xlive, lmarks if r > 0 else None)                  # the first one warms up
+        torch.cuda.synchronize()
+        lms = sorted(e[0].elapsed_time(e[3]) for e in lmarks)
+        net.sdnn_forward(xlive, xl)
+        lact = {f"layer_{k}": round(float((net.sdnn_get_activation(k, Bt) != 0).float().mean()), 4)
+                for k in sorted({1, min(2, L), L})}
+        for k in range(1, L + 1):
+            net.sdnn_set_weights(k, saved[k - 1][0], saved[k - 1][1])
+        live = {"input_density": d_live, "step_ms_median": round(lms[len(lms) // 2], 4), "step_ms_min": round(lms[0], 4),
+                "edges_per_s": nnz_total * Bt / (lms[len(lms) // 2] * 1e-3), "reps": reps,
+                "weights_restored_between_reps": True, "active_fraction": lact}
+        del saved, xlive
+        log(f"config {cfg}: live inputs (density {d_live}) step {live['step_ms_median']:.3f} ms")
 
     # ---- roofline of the dominant kernel --------------------------------
     fb = bb = ub = 0
     for lay in work.layers:
-        f, b, u = layer_bytes(lay.n_out, lay.nnz, Bt)
+        f, b, u = layer_bytes(lay.n_out, lay.nnz, Bt, fused)
         fb += f; bb += b; ub += u
-    passes = {"forward": (fwd_ms, fb, L), "backward": (bwd_ms, bb - layer_bytes(N, work.layers[0].nnz, Bt)[1], L - 1),
-              "update": (upd_ms, ub, 1)}
+    first = work.layers[0]
+    # separate backward: layers L..2 only; fused sweep: all layers, the first one without a Delta output
+    bb -= (4 * first.n_in * Bt) if fused else layer_bytes(first.n_out, first.nnz, Bt, fused)[1]
+    kernels = {"forward": f"k_spmm<{v},0,{8 if short_rows else 16}>",
+               "backward": "k_bwd_grad<8>" if fused else f"k_spmm<{v},1,{8 if short_rows else 16}>",
+               "update": "k_apply + k_apply_bias" if fused else "k_update<4>"}
+    passes = {"forward": (fwd_ms, fb, L), "backward": (bwd_ms, bb, L if fused else L - 1), "update": (upd_ms, ub, 1)}
     dom = max(passes, key=lambda k: passes[k][0])
-    d_ms, d_bytes, d_launches = passes[dom]
+    d_ms, d_bytes, d_units = passes[dom]
     achieved = d_bytes / (d_ms * 1e-3) / 1e9
-    # measured HBM-side bytes per launch of that kernel (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the
-    # copy-kernel calibration), taken from the committed counter summary of this same workload
+    # measured HBM-side bytes per unit of that pass (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the
+    # copy-kernel calibration), from the committed counter summary of this same workload
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"config{args.config}_traffic.json")
-    if os.path.exists(tpath) and args.layers is None and args.density is None:
+    tpath = os.path.join(ROOT, "profiles", f"config{cfg}_traffic.json")
+    if os.path.exists(tpath) and density_arg is None:
         t = json.load(open(tpath))
-        k = t["kernels"][dom]
-        traffic = int(1024 * (k["fetch_KiB"] * t["scale"]["FETCH_SIZE"] + k["write_KiB"] * t["scale"]["WRITE_SIZE"]))
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        k = t["kernels"].get(dom)
+        if k:
+            traffic = int(1024 * (k["fetch_KiB"] * t["scale"]["FETCH_SIZE"] + k["write_KiB"] * t["scale"]["WRITE_SIZE"]))
+    roofline = {"bound": "hbm", "kernel": kernels[dom], "pass": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "binding_unit": "vector L1 gather path (~30 B/clk/CU, see profiles/config2_counters.md)",
-                "units_per_step": d_launches, "unit_of_work": "one layer" if dom != "update" else "all layers",
-                "avg_unit_us": round(d_ms * 1e3 / d_launches, 3), "bytes_per_unit": int(d_bytes / d_launches),
-                # forward/backward over small layers: each layer is two half-batch launches on two streams
-                "kernel_launches_per_unit": 2 if (dom != "update" and Bt % 128 == 0 and N * Bt <= 2 ** 21) else 1}
+                "units_per_step": d_units, "unit_of_work": "one layer" if dom != "update" else "all layers",
+                "avg_unit_us": round(d_ms * 1e3 / d_units, 3), "bytes_per_unit": int(d_bytes / d_units),
+                "kernel_launches_per_unit": 2 if (dom != "update" and split) else 1,
+                "per_pass_frac": {p: round(passes[p][1] / (passes[p][0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for p in passes},
+                "step_frac": round((fb + bb + ub) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     net.close()
-    del net
+    del net, x0
+    torch.cuda.empty_cache()
 
     # ---- inference forward over the full sample set ----------------------
     infer = None
     if not args.no_inference:
-        block = args.infer_block or min(Bi, 1024 if N >= 65536 else Bi)
+        block = (args.infer_block if headline else 0) or min(Bi, 1024 if N >= 65536 else Bi)
+        t0 = time.time()
         inet = sdnn.Net(work.layers, work.act_cap, block, training=False)
-        xi = to_dev(work.x_infer)
+        torch.cuda.synchronize()
+        icreate_s = time.time() - t0
         blocks = [(s, min(block, Bi - s)) for s in range(0, Bi, block)]
-        xin = [xi[:, s:s + w].contiguous() for s, w in blocks]
+        xin = [to_dev(work.x_infer[:, s:s + w]) for s, w in blocks]
         xout = [torch.empty(work.layers[-1].n_out, w, device=dev) for s, w in blocks]
 
         def infer_pass():
             for a, o in zip(xin, xout):
                 inet.sdnn_forward(a, o)
 
-        for _ in range(max(1, args.warmup)):
-            infer_pass()
+        infer_pass()
         torch.cuda.synchronize()
-        k = max(3, args.steps // 2)
+        k = max(3, steps // 4)
         t0 = time.perf_counter()
         for _ in range(k):
             infer_pass()
         torch.cuda.synchronize()
         ims = (time.perf_counter() - t0) * 1e3 / k
-        ibytes = sum(layer_bytes(l.n_out, l.nnz, Bi)[0] for l in work.layers)
+        ibytes = sum(layer_bytes(l.n_out, l.nnz, Bi, False)[0] for l in work.layers)
         infer = {"edges_per_s": nnz_total * Bi / (ims * 1e-3), "ms": round(ims, 3), "samples": Bi,
                  "block": block, "algorithmic_GBs": round(ibytes / (ims * 1e-3) / 1e9, 1),
-                 "hbm_frac": round(ibytes / (ims * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                 "hbm_frac": round(ibytes / (ims * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "create_s": round(icreate_s, 2)}
+        log(f"config {cfg}: inference {ims:.3f} ms for {Bi} samples, {infer['edges_per_s']:.3e} edges/s")
         # second figure, never the headline: the same inference with dead samples dropped (ReLU, biases <= 0);
         # the edge count in the numerator then includes edges that were never visited
         if not args.no_skip_dead and work.activation == "relu" and all((l.bias <= 0).all() for l in work.layers[1:]):
             n_live = torch.zeros(1, dtype=torch.int32, device=dev)
             xchk = [torch.empty_like(o) for o in xout]
-
-            def skip_pass(outs):
-                for a, o in zip(xin, outs):
-                    inet.sdnn_forward_skip_dead(a, o, check_every=args.check_every, n_live=n_live)
-
-            skip_pass(xchk)
-            same = all(torch.equal(a, b) for a, b in zip(xout, xchk))
             live_end = 0
             for a, o in zip(xin, xchk):
                 inet.sdnn_forward_skip_dead(a, o, check_every=args.check_every, n_live=n_live)
                 live_end += int(n_live.item())
+            same = all(torch.equal(a, b) for a, b in zip(xout, xchk))
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(k):
-                skip_pass(xchk)
+                for a, o in zip(xin, xchk):
+                    inet.sdnn_forward_skip_dead(a, o, check_every=args.check_every, n_live=n_live)
             torch.cuda.synchronize()
             sms = (time.perf_counter() - t0) * 1e3 / k
             infer["skip_dead"] = {"edges_per_s": nnz_total * Bi / (sms * 1e-3), "ms": round(sms, 3),
                                   "check_every": args.check_every, "live_samples_at_last_check": live_end,
                                   "identical_to_plain_forward": bool(same)}
+            del xchk
         inet.close()
-        del inet
+        del inet, xin, xout
+        torch.cuda.empty_cache()
 
-    # ---- the oracle on the host cores, as a baseline ----------------------
+    # ---- the oracle on the host cores, as a baseline (headline workload only) ----------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if headline and not args.no_cpu_baseline:
         from oracle.sdnn_oracle import Oracle, mse_dloss, softmax_ce_dloss
         orc = Oracle(np.float32)
         if work.loss == "mse":
-            dfn = lambda x: mse_dloss(x, work.targets)
+            dfn = lambda x: mse_dloss(x, work.targets)          # same shape at any depth: the net is square
         else:
             dfn = lambda x: softmax_ce_dloss(x, work.labels, work.n_classes)
-        # bounded sample: a depth prefix worth about 3e10 edge visits (10-30 s of CPU work)
+        # bounded sample: a depth prefix worth about 1.5e10 edge visits (10-30 s of CPU work)
         per_layer = 3.0 * (nnz_total / L) * Bt
-        Ls = int(max(1, min(L, 3e10 // per_layer)))
+        Ls = int(max(1, min(L, args.cpu_edge_visits // per_layer)))
         sub = work.layers[:Ls]
-        if work.loss == "mse":
-            dfn = lambda x: mse_dloss(x, work.targets)      # same shape: the net is square
         t0 = time.perf_counter()
         orc.train_step(sub, work.x_train, work.act_cap, dfn, work.lr)
         cs = time.perf_counter() - t0
         cpu = {"value": sum(l.nnz for l in sub) * Bt / cs, "unit": "edges/s", "cores": orc.threads(),
                "kind": "oracle",
                "sample": f"one training step on the first {Ls} of {L} layers, full minibatch {Bt} ({cs:.1f} s)"}
-        # the same oracle on one thread, on a shorter depth prefix (about 1.5e9 edge visits)
+        # the same oracle on one thread, on a shorter depth prefix
         n_all = orc.threads()
-        L1 = int(max(1, min(Ls, 1.5e9 // per_layer)))
+        L1 = int(max(1, min(Ls, (args.cpu_edge_visits / 20) // per_layer)))
         orc.set_threads(1)
         t0 = time.perf_counter()
         orc.train_step(work.layers[:L1], work.x_train, work.act_cap, dfn, work.lr)
@@ -234,21 +289,92 @@ def main():
         orc.set_threads(n_all)
         cpu["single_thread"] = {"value": sum(l.nnz for l in work.layers[:L1]) * Bt / c1, "unit": "edges/s",
                                 "sample": f"first {L1} layers ({c1:.1f} s)"}
+        log(f"config {cfg}: oracle {cpu['value']:.3e} edges/s on {cpu['cores']} threads ({cs:.1f} s)")
+
+    return {
+        "workload": workload_name(cfg, N, L), "train_batch": Bt, "infer_samples": Bi, "total_nnz": nnz_total,
+        "input_density": work.meta.get("density"), "active_fraction": active,
+        "ms_per_step": round(ms_step, 4), "step_ms_min": round(per_step[0], 4),
+        "step_ms_median": round(per_step[len(per_step) // 2], 4), "edges_per_s": train_eps, "steps": steps,
+        "weights_unchanged_by_the_timed_steps": bool(unchanged), "gradient_formed_in_backward_sweep": bool(fused),
+        "pass_ms": {"forward": round(fwd_ms, 4), "backward": round(bwd_ms, 4), "update": round(upd_ms, 4)},
+        "live_inputs": live, "inference": infer, "roofline": roofline, "cpu_baseline": cpu,
+        "setup_s": {"generate": round(gen_s, 2), "create": round(create_s, 2)},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (the headline workload)")
+    ap.add_argument("--layers", type=int, default=None, help="depth prefix (default: full depth)")
+    ap.add_argument("--density", type=float, default=None, help="input density override (live inputs)")
+    ap.add_argument("--paper-setup", action="store_true",
+                    help="the paper's own training experiment: sigmoid, weights U[-1,1], one input vector per step")
+    ap.add_argument("--n", type=int, default=1024, help="neurons per layer for --paper-setup")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-edge-visits", type=float, default=1.5e10,
+                    help="size of the oracle's bounded sample, in edge visits (3 per edge-sample of a step)")
+    ap.add_argument("--check-every", type=int, default=4,
+                    help="layers between two packings of the live samples in the skip-dead inference figure")
+    ap.add_argument("--infer-block", type=int, default=0,
+                    help="samples per sdnn_forward call of the inference figure (0: all, 1024 for N >= 65536)")
+    ap.add_argument("--no-inference", action="store_true")
+    ap.add_argument("--no-skip-dead", action="store_true", help="leave out the skip-dead inference figure")
+    ap.add_argument("--no-live", action="store_true", help="leave out the live-input repetition of the step")
+    ap.add_argument("--others", type=str, default=None,
+                    help="comma-separated configurations for the key other_configs (default: the other four when "
+                         "the headline runs at full depth with nominal inputs; 'none' for none)")
+    ap.add_argument("--time-budget", type=float, default=400.0,
+                    help="seconds since program start after which no further other_configs entry is begun")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2104_11805_amd import sdnn, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    log("torch and the library are loaded")
+    if args.paper_setup:
+        return paper_setup_bench(args, np, torch, sdnn, wl)
+
+    head = run_config(args.config, args, args.steps, args.warmup, headline=True)
+    if args.others is None:
+        others = [c for c in (3, 5, 2, 1) if c != args.config] if (args.layers is None and args.density is None) else []
+    else:
+        others = [] if args.others == "none" else [int(c) for c in args.others.split(",")]
+    other_configs = {}
+    for c in others:
+        if time.time() - T_START > args.time_budget:
+            other_configs[f"config {c}"] = {"skipped": f"time budget of {args.time_budget:.0f} s used up"}
+            continue
+        r = run_config(c, args, max(5, args.steps // 2), max(1, args.warmup - 1), headline=False)
+        r.pop("cpu_baseline")
+        other_configs[f"config {c}"] = r
 
     out = {
         "metric": "edges/s, forward+backward+SGD step (nnz x samples / time)",
-        "value": train_eps, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 4), "step_ms_min": round(per_step[0], 4),
-        "step_ms_median": round(per_step[len(per_step) // 2], 4), "edge_visits_per_s": 3.0 * train_eps,
+        "value": head["edges_per_s"], "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "step_ms_min": head["step_ms_min"],
+        "step_ms_median": head["step_ms_median"], "edge_visits_per_s": 3.0 * head["edges_per_s"],
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: N={N}, L={L}, 32 nnz/row" if args.config < 5
-                   else f"config 5: N={N}, L={L}, heavy-tailed rows",
-                   "train_batch": Bt, "infer_samples": Bi, "total_nnz": nnz_total,
-                   "storage": "fp32", "accumulate": "fp64", "input_density": work.meta.get("density"), "active_fraction": active},
-        "pass_ms": {"forward": round(fwd_ms, 4), "backward": round(bwd_ms, 4), "update": round(upd_ms, 4)},
-        "inference": infer, "roofline": roofline, "cpu_baseline": cpu,
-        "setup_s": {"generate": round(gen_s, 2)},
+        "config": {"workload": head["workload"], "train_batch": head["train_batch"],
+                   "infer_samples": head["infer_samples"], "total_nnz": head["total_nnz"],
+                   "storage": "fp32", "accumulate": "fp64", "input_density": head["input_density"],
+                   "active_fraction": head["active_fraction"],
+                   "weights_unchanged_by_the_timed_steps": head["weights_unchanged_by_the_timed_steps"],
+                   "gradient_formed_in_backward_sweep": head["gradient_formed_in_backward_sweep"]},
+        "pass_ms": head["pass_ms"], "live_inputs": head["live_inputs"],
+        "inference": head["inference"], "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
+        "setup_s": head["setup_s"], "other_configs": other_configs,
+        "total_s": round(time.time() - T_START, 1),
     }
     print(json.dumps(out))
 

@@ -139,7 +139,7 @@ class Oracle:
 
     # ---- Algorithm 1 ----------------------------------------------------
     def forward(self, layers: Sequence, x0: np.ndarray, cap: float) -> List[np.ndarray]:
-        """Lines 2-4: returns [X_0, X_1, ..., X_L]."""
+        """Feed-forward sweep (Eq. 3 for k = 1..L): returns [X_0, X_1, ..., X_L]."""
         xs = [self._arr(x0)]
         for layer in layers:
             xs.append(self.forward_layer(layer, xs[-1], cap))
@@ -156,11 +156,11 @@ class Oracle:
         return deltas
 
     def gradients(self, layers: Sequence, xs, deltas):
-        """Line 8 for every layer: [(g_k, gb_k)] for k = 1..L (list index k-1)."""
+        """Eq. 4 for every layer: [(g_k, gb_k)] for k = 1..L (list index k-1)."""
         return [self.weight_grad(layers[k - 1], deltas[k], xs[k - 1]) for k in range(1, len(layers) + 1)]
 
     def sgd_step(self, layers: Sequence, grads, lr: float, update_bias: bool = True):
-        """Line 9: new (values, bias) per layer; the pattern is never touched."""
+        """Eq. 5 (descent step): new (values, bias) per layer; the pattern is never touched."""
         out = []
         for layer, (g, gb) in zip(layers, grads):
             v = self.sgd_apply(layer.values, g, lr)

@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libsdnn.so")
 SOURCES = ["sdnn.hip", "sdnn_setup.cpp"]
 
 # packed-fp32 instruction selection is switched off for all device code
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument"]
 

@@ -27,7 +27,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
+#include <functional>
 #include <new>
+#include <thread>
 #include <vector>
 
 #include "sdnn_internal.h"
@@ -111,6 +114,16 @@ __device__ __forceinline__ float act_backprop(int act, double value, float x, fl
         return (float)(value * (xd * (1.0 - xd)));
     }
     return (x > 0.0f && x < capf) ? (float)value : 0.0f;
+}
+
+// Orders the LDS (or in-place global) accesses of the lanes of one wavefront: what the lanes wrote before
+// is visible to the other lanes after, and nothing is moved across.  Costs no instruction beyond the wait
+// for the outstanding accesses.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Workgroup ids are handed to the 8 XCDs round-robin and each XCD has its own
@@ -323,6 +336,139 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// K1p / K2p: the same product for wide layers with short rows, swept in column panels.
+//
+// A 64-sample tile of a wide layer's operand (n_cols x 256 B) is several times the 4 MiB L2 of an
+// XCD, and a row's 32 or so gathers land all over it, so without further care most gathers miss
+// L2.  Here a wavefront owns R rows and keeps their entries (entry k of a row in lane k) and their
+// R accumulators in registers; it walks the operand in panels of panel_cols rows, and in each
+// panel every one of its rows consumes the entries whose column falls into the panel.  Column
+// indices ascend inside a row, so each row still adds its terms in storage order: the sums are the
+// same as in k_spmm.  The wavefronts resident on an XCD advance through the panels at about the
+// same pace (nothing enforces it: a wavefront that runs ahead or behind only loses L2 hits), so
+// an XCD's L2 holds one panel at a time and pulls each operand row in once per launch.
+// Rows must have at most 64 entries (checked by the host); one sample per lane.
+// ---------------------------------------------------------------------------
+#define PANEL_SLOTS 8 // gathers of one row segment that are in flight together; longer segments go round again
+
+// Requests the operand rows of entries k .. min(k + PANEL_SLOTS, ke) - 1 of a row (wave-uniform branches).
+__device__ __forceinline__ void panel_issue(__amdgpu_buffer_rsrc_t rin, unsigned so, unsigned ldb, int c_l, int k, int ke,
+                                            float (&x)[PANEL_SLOTS])
+{
+#define PANEL_G(j) x[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rin, (int)so, (int)((unsigned)__builtin_amdgcn_readlane(c_l, k + j) * ldb), 0))
+    const int n = ke - k;
+    if (n > 0) { PANEL_G(0);
+    if (n > 1) { PANEL_G(1);
+    if (n > 2) { PANEL_G(2);
+    if (n > 3) { PANEL_G(3);
+    if (n > 4) { PANEL_G(4);
+    if (n > 5) { PANEL_G(5);
+    if (n > 6) { PANEL_G(6);
+    if (n > 7) { PANEL_G(7); } } } } } } } }
+#undef PANEL_G
+}
+
+// Adds the terms of the same entries, in storage order.
+__device__ __forceinline__ void panel_consume(float w_l, int k, int ke, const float (&x)[PANEL_SLOTS], double &acc)
+{
+#define PANEL_F(j) acc = fma((double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_l), k + j)), (double)x[j], acc)
+    const int n = ke - k;
+    if (n > 0) { PANEL_F(0);
+    if (n > 1) { PANEL_F(1);
+    if (n > 2) { PANEL_F(2);
+    if (n > 3) { PANEL_F(3);
+    if (n > 4) { PANEL_F(4);
+    if (n > 5) { PANEL_F(5);
+    if (n > 6) { PANEL_F(6);
+    if (n > 7) { PANEL_F(7); } } } } } } } }
+#undef PANEL_F
+}
+
+template <int R, int MODE>
+__global__ void __launch_bounds__(BLOCK_THREADS) k_spmm_panel(const SpmmArgs a, int n_cols, int panel_cols)
+{
+    const int lane = threadIdx.x & 63;
+    const unsigned wave = threadIdx.x >> 6;
+    const int B = a.B;
+    const size_t ld = (size_t)B;
+    const unsigned ldb = 4u * (unsigned)B;
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
+    for (unsigned vb = blockIdx.x; vb < a.n_vblocks; vb += gridDim.x) {
+        unsigned tile, rg;
+        map_block(vb, a.n_tiles, a.n_rg, tile, rg); // n_rg counts groups of WAVES_PER_BLOCK * R rows here
+        const int r0 = __builtin_amdgcn_readfirstlane((int)((rg * WAVES_PER_BLOCK + wave) * R));
+        if (r0 >= a.n_rows) continue;
+        const int s_own = (int)(tile + a.tile_base) * 64 + lane;
+        const bool live = s_own < B;
+        const int s = live ? s_own : 0;
+        const unsigned so = 4u * (unsigned)s;
+
+        int row[R], c_l[R], kcur[R];
+        float w_l[R], xp[R];
+        double acc[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            row[r] = -1;
+            c_l[r] = 0x7fffffff; // past every panel: lanes beyond the end of a row, and rows beyond the last
+            w_l[r] = 0.0f;
+            xp[r] = 0.0f;
+            acc[r] = 0.0;
+            kcur[r] = 0;
+            if (r0 + r < a.n_rows) {
+                const int4 t = a.sched[r0 + r];
+                row[r] = t.x;
+                if (t.y + lane < t.z) {
+                    c_l[r] = a.idx[t.y + lane];
+                    w_l[r] = MODE == 1 ? a.vals[a.perm[t.y + lane]] : a.vals[t.y + lane];
+                }
+                if (MODE == 1) xp[r] = a.aux[(size_t)t.x * ld + s];
+            }
+        }
+        for (int pe = panel_cols;; pe += panel_cols) {
+            const bool last = pe >= n_cols;
+            const int bound = last ? 0x7fffffff : pe;
+#pragma unroll
+            for (int r = 0; r < R; r += 2) {
+                // columns ascend inside a row: the entries below the bound are a prefix of the lanes
+                const int ke0 = (int)__popcll(__ballot(c_l[r] < bound));
+                int k0 = kcur[r];
+                kcur[r] = ke0;
+                float x0[PANEL_SLOTS];
+                panel_issue(rin, so, ldb, c_l[r], k0, ke0, x0);
+                if constexpr (R > 1) {
+                    const int ke1 = (int)__popcll(__ballot(c_l[r + 1] < bound));
+                    int k1 = kcur[r + 1];
+                    kcur[r + 1] = ke1;
+                    float x1[PANEL_SLOTS];
+                    panel_issue(rin, so, ldb, c_l[r + 1], k1, ke1, x1);
+                    panel_consume(w_l[r], k0, ke0, x0, acc[r]);
+                    panel_consume(w_l[r + 1], k1, ke1, x1, acc[r + 1]);
+                    for (k1 += PANEL_SLOTS; k1 < ke1; k1 += PANEL_SLOTS) {
+                        panel_issue(rin, so, ldb, c_l[r + 1], k1, ke1, x1);
+                        panel_consume(w_l[r + 1], k1, ke1, x1, acc[r + 1]);
+                    }
+                } else {
+                    panel_consume(w_l[r], k0, ke0, x0, acc[r]);
+                }
+                for (k0 += PANEL_SLOTS; k0 < ke0; k0 += PANEL_SLOTS) {
+                    panel_issue(rin, so, ldb, c_l[r], k0, ke0, x0);
+                    panel_consume(w_l[r], k0, ke0, x0, acc[r]);
+                }
+            }
+            if (last) break;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (row[r] < 0) continue;
+            float o;
+            if (MODE == 0) o = act_apply(a.act, acc[r] + (a.aux ? (double)a.aux[row[r]] : 0.0), a.cap);
+            else o = act_backprop(a.act, acc[r], xp[r], a.cap);
+            if (live) a.out[(size_t)row[r] * ld + s] = o;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // K2 + K4a: back-propagation through W_l fused with the gradient of W_l's stored entries, for
 // launches of at most 64 samples (one sample per lane).  The wavefront of row i of W_l^T gathers
 // Delta_l(j, :) for every stored entry (j, i) anyway and holds X_{l-1}(i, :), the two operands of
@@ -390,7 +536,9 @@ __device__ __forceinline__ void spmm_row_grad(RowMeta m, const SpmmArgs &a, unsi
                         }
                 }
             }
-            // entry e of this group, samples 16q .. 16q+15 (LDS operations of one wavefront complete in order)
+            // entry e of this group, samples 16q .. 16q+15: the lanes now read what other lanes of the
+            // wavefront have parked
+            wave_lds_sync();
             double sum = 0.0;
             if (e < ng) {
                 const float4 *dp = reinterpret_cast<const float4 *>(dt + e * GRAD_LD + 16 * q);
@@ -408,6 +556,7 @@ __device__ __forceinline__ void spmm_row_grad(RowMeta m, const SpmmArgs &a, unsi
             sum += __shfl_xor(sum, 32);
             const int pos = __shfl(p_l, g0 + e); // CSR position of entry e, held by lane g0 + e
             if (q == 0 && e < ng) a.g_part[pos] = (float)sum;
+            wave_lds_sync(); // the next group's rows are parked over the ones just read
         }
     }
     if (a.store_out && live) a.out[(size_t)m.row * ld + s] = act_backprop(a.act, acc, xp, a.cap);
@@ -740,8 +889,21 @@ __global__ void __launch_bounds__(256) k_apply(const LayerDev *__restrict__ laye
     }
 }
 
+// The gradient that k_apply applies, for inspection: out = g0 (+ g1), the same rounding as in k_apply.
+__global__ void __launch_bounds__(256) k_sum_parts(const float *__restrict__ g0, const float *__restrict__ g1,
+                                                   float *__restrict__ out, int n)
+{
+    for (int p = blockIdx.x * 256 + threadIdx.x; p < n; p += gridDim.x * 256) {
+        double g = (double)g0[p];
+        if (g1) g += (double)g1[p];
+        out[p] = (float)g;
+    }
+}
+
 // 16 lanes per row, four rows per wavefront at a time, 16 consecutive rows per wavefront.
-__global__ void __launch_bounds__(BLOCK_THREADS) k_apply_bias(const LayerDev *__restrict__ layers, int B, float lr)
+// gb_out == NULL: bias -= lr * gb; otherwise the bias gradient of the one layer is stored there instead.
+__global__ void __launch_bounds__(BLOCK_THREADS) k_apply_bias(const LayerDev *__restrict__ layers, int B, float lr,
+                                                              float *__restrict__ gb_out)
 {
     const LayerDev &L = layers[blockIdx.y];
     const int lane = threadIdx.x & 63, l = lane & 15;
@@ -763,7 +925,10 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_apply_bias(const LayerDev *__
         }
 #pragma unroll
         for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-        if (l == 0 && row < L.n_out) L.bias[row] = (float)((double)L.bias[row] - (double)lr * (double)(float)sum);
+        if (l == 0 && row < L.n_out) {
+            if (gb_out) gb_out[row] = (float)sum;
+            else L.bias[row] = (float)((double)L.bias[row] - (double)lr * (double)(float)sum);
+        }
     }
 }
 
@@ -837,6 +1002,7 @@ __global__ void __launch_bounds__(256) k_pack(float *X, int n_rows, int ld, cons
             int np = -1;
             float v = 0.0f;
             if (c < nl) { np = newpos[c]; v = row[c]; }
+            wave_lds_sync(); // every lane has read its column before any lane overwrites one
             if (np >= 0) row[np] = v;
         }
     }
@@ -910,6 +1076,9 @@ struct sdnn_net {
     int n_cu = 0;                 // compute units of the device
     int occ_spmm[2][3][2] = {}; // resident workgroups per CU of k_spmm<V,MODE,8,tiles inner>
     int occ_grad = 0;             // the same for k_bwd_grad
+    int occ_panel[2][4] = {};     // the same for k_spmm_panel<R,MODE>, R = 1, 2, 4, 8
+    std::vector<int32_t> max_len[2]; // per layer: longest row of W (0) and of W^T (1)
+    int panel_cols = 0, panel_r = 0; // experiment knobs (environment), 0 = policy
     int grad_parts = 0;           // > 0: the last backward pass left the entries' gradient in G[0..grad_parts)
     hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -1048,7 +1217,11 @@ extern "C" int sdnn_workspace_bytes(const sdnn_layer *layers, int32_t n_layers,
         if (layers[l].row_ptr[0] != 0 || layers[l].row_ptr[layers[l].n_out] < 0)
             return fail(nullptr, SDNN_EINVAL, "layer %d: malformed row_ptr", l + 1);
     Plan pl;
-    make_plan(layers, n_layers, cfg, pl);
+    try {
+        make_plan(layers, n_layers, cfg, pl);
+    } catch (...) {
+        return fail(nullptr, SDNN_ENOMEM, "host allocation failed");
+    }
     *bytes = pl.total;
     return SDNN_OK;
 }
@@ -1071,7 +1244,11 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     if (((uintptr_t)d_workspace & 255) != 0)
         return fail(nullptr, SDNN_EINVAL, "d_workspace must be 256-byte aligned");
     Plan pl;
-    make_plan(layers, n_layers, cfg, pl);
+    try {
+        make_plan(layers, n_layers, cfg, pl);
+    } catch (...) {
+        return fail(nullptr, SDNN_ENOMEM, "host allocation failed");
+    }
     if (workspace_bytes < pl.total)
         return fail(nullptr, SDNN_ENOMEM, "workspace too small: %zu < %zu", workspace_bytes, pl.total);
 
@@ -1080,78 +1257,136 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     if (!net) return fail(nullptr, SDNN_ENOMEM, "host allocation failed");
     net->n_layers = n_layers;
     net->cfg = *cfg;
-    net->layers.resize(n_layers);
+    try {
+        net->layers.resize(n_layers);
+        net->max_len[0].resize(n_layers);
+        net->max_len[1].resize(n_layers);
+    } catch (...) {
+        delete net;
+        return fail(nullptr, SDNN_ENOMEM, "host allocation failed");
+    }
     char *base = (char *)d_workspace;
     auto fail_free = [&](int code) { sdnn_destroy(net); return code; };
 
-    std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
-    std::vector<int4> sched, t_sched;
-    std::vector<float> zeros;
-    for (int32_t l = 0; l < n_layers; ++l) {
-        const sdnn_layer &y = layers[l];
-        const Plan::PerLayer &q = pl.pl[l];
-        const size_t nnz = (size_t)y.row_ptr[y.n_out];
-        t_row_ptr.resize((size_t)y.n_in + 1);
-        t_row_idx.resize(nnz);
-        t_perm.resize(nnz);
-        order.resize(y.n_out);
-        t_order.resize(y.n_in);
-        sdnn_transpose_pattern(y.n_out, y.n_in, y.row_ptr, y.col_idx, t_row_ptr.data(),
-                               t_row_idx.data(), t_perm.data());
-        sdnn_row_schedule(y.n_out, y.row_ptr, order.data());
-        sdnn_row_schedule(y.n_in, t_row_ptr.data(), t_order.data());
-        sched.resize(y.n_out);
-        t_sched.resize(y.n_in);
-        for (int32_t r = 0; r < y.n_out; ++r)
-            sched[r] = make_int4(order[r], y.row_ptr[order[r]], y.row_ptr[order[r] + 1], 0);
-        for (int32_t r = 0; r < y.n_in; ++r)
-            t_sched[r] = make_int4(t_order[r], t_row_ptr[t_order[r]], t_row_ptr[t_order[r] + 1], 0);
-
-        LayerDev &d = net->layers[l];
-        d.n_out = y.n_out; d.n_in = y.n_in; d.nnz = (int32_t)nnz; d.pad_ = 0;
-        d.row_ptr = (const int32_t *)(base + q.row_ptr);
-        d.col_idx = (const int32_t *)(base + q.col_idx);
-        d.vals = (float *)(base + q.vals);
-        d.bias = (float *)(base + q.bias);
-        d.t_row_ptr = (const int32_t *)(base + q.t_row_ptr);
-        d.t_row_idx = (const int32_t *)(base + q.t_row_idx);
-        d.t_perm = (const int32_t *)(base + q.t_perm);
-        d.sched = (const int4 *)(base + q.sched);
-        d.t_sched = (const int4 *)(base + q.t_sched);
-        d.X = cfg->training ? (float *)(base + q.X) : nullptr;
-        d.D = cfg->training ? (float *)(base + q.D) : nullptr;
-        const bool gw = grad_buffers_wanted(layers, n_layers, cfg);
-        d.G[0] = gw ? (float *)(base + q.G[0]) : nullptr;
-        d.G[1] = gw ? (float *)(base + q.G[1]) : nullptr;
-        d.X_prev = !cfg->training ? nullptr
-                   : l == 0       ? (float *)(base + pl.x0)
-                                  : net->layers[l - 1].X;
-        net->max_n = std::max(net->max_n, std::max(y.n_out, y.n_in));
-
-        const float *bias = y.bias;
-        if (!bias) { zeros.assign((size_t)y.n_out, 0.0f); bias = zeros.data(); }
+    // Host part of the setup (transposed index, row schedules): independent per layer, so a group of layers is
+    // prepared by one host thread each, then uploaded with one synchronisation for the whole group.
+    struct HostIdx {
+        std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
+        std::vector<int4> sched, t_sched;
+        int32_t max_len = 0, t_max_len = 0;
+        int rc = SDNN_OK;
+    };
+    auto prepare = [&](int32_t l, HostIdx &h) {
+        try {
+            const sdnn_layer &y = layers[l];
+            const size_t nnz = (size_t)y.row_ptr[y.n_out];
+            h.t_row_ptr.resize((size_t)y.n_in + 1);
+            h.t_row_idx.resize(nnz);
+            h.t_perm.resize(nnz);
+            h.order.resize(y.n_out);
+            h.t_order.resize(y.n_in);
+            h.sched.resize(y.n_out);
+            h.t_sched.resize(y.n_in);
+            h.rc = sdnn_transpose_pattern(y.n_out, y.n_in, y.row_ptr, y.col_idx, h.t_row_ptr.data(),
+                                          h.t_row_idx.data(), h.t_perm.data());
+            if (h.rc) return;
+            sdnn_row_schedule(y.n_out, y.row_ptr, h.order.data());
+            sdnn_row_schedule(y.n_in, h.t_row_ptr.data(), h.t_order.data());
+            for (int32_t r = 0; r < y.n_out; ++r)
+                h.sched[r] = make_int4(h.order[r], y.row_ptr[h.order[r]], y.row_ptr[h.order[r] + 1], 0);
+            for (int32_t r = 0; r < y.n_in; ++r)
+                h.t_sched[r] = make_int4(h.t_order[r], h.t_row_ptr[h.t_order[r]], h.t_row_ptr[h.t_order[r] + 1], 0);
+            // the schedules list the rows longest first
+            h.max_len = y.n_out > 0 ? h.sched[0].z - h.sched[0].y : 0;
+            h.t_max_len = y.n_in > 0 ? h.t_sched[0].z - h.t_sched[0].y : 0;
+        } catch (...) {
+            h.rc = SDNN_ENOMEM;
+        }
+    };
 #define UP(dst, src, bytes)                                                                   \
     do {                                                                                      \
         if ((bytes) > 0) {                                                                    \
             hipError_t e_ = hipMemcpyAsync((void *)(dst), (src), (bytes), hipMemcpyHostToDevice, stream); \
-            if (e_ == hipSuccess) e_ = hipStreamSynchronize(stream);                          \
             if (e_ != hipSuccess)                                                             \
                 return fail_free(fail(nullptr, SDNN_EHIP, "upload: %s", hipGetErrorString(e_))); \
         }                                                                                     \
     } while (0)
-        UP(d.row_ptr, y.row_ptr, 4 * ((size_t)y.n_out + 1));
-        UP(d.col_idx, y.col_idx, 4 * nnz);
-        UP(d.vals, y.values, 4 * nnz);
-        UP(d.bias, bias, 4 * (size_t)y.n_out);
-        UP(d.t_row_ptr, t_row_ptr.data(), 4 * ((size_t)y.n_in + 1));
-        UP(d.t_row_idx, t_row_idx.data(), 4 * nnz);
-        UP(d.t_perm, t_perm.data(), 4 * nnz);
-        UP(d.sched, sched.data(), 16 * (size_t)y.n_out);
-        UP(d.t_sched, t_sched.data(), 16 * (size_t)y.n_in);
+#define SYNC()                                                                                \
+    do {                                                                                      \
+        hipError_t e_ = hipStreamSynchronize(stream);                                         \
+        if (e_ != hipSuccess)                                                                 \
+            return fail_free(fail(nullptr, SDNN_EHIP, "upload: %s", hipGetErrorString(e_)));  \
+    } while (0)
+    try {
+        const bool gw = grad_buffers_wanted(layers, n_layers, cfg);
+        int32_t max_out = 0;
+        for (int32_t l = 0; l < n_layers; ++l) max_out = std::max(max_out, layers[l].n_out);
+        const std::vector<float> zeros((size_t)max_out, 0.0f); // stands in for a NULL bias
+        unsigned hw = std::thread::hardware_concurrency();
+        const int32_t group = (int32_t)std::max(1u, std::min({hw ? hw : 1u, 16u, (unsigned)n_layers}));
+        std::vector<HostIdx> idx((size_t)group);
+        for (int32_t l0 = 0; l0 < n_layers; l0 += group) {
+            const int32_t ng = std::min(group, n_layers - l0);
+            {
+                std::vector<std::thread> workers;
+                for (int32_t k = 1; k < ng; ++k) {
+                    try {
+                        workers.emplace_back(prepare, l0 + k, std::ref(idx[k]));
+                    } catch (...) { // no more threads: do it here
+                        prepare(l0 + k, idx[k]);
+                    }
+                }
+                prepare(l0, idx[0]);
+                for (std::thread &w : workers) w.join();
+            }
+            for (int32_t k = 0; k < ng; ++k) {
+                const int32_t l = l0 + k;
+                const HostIdx &h = idx[k];
+                if (h.rc) return fail_free(fail(nullptr, h.rc, "layer %d: host setup failed (out of memory?)", l + 1));
+                const sdnn_layer &y = layers[l];
+                const Plan::PerLayer &q = pl.pl[l];
+                const size_t nnz = (size_t)y.row_ptr[y.n_out];
+                LayerDev &d = net->layers[l];
+                d.n_out = y.n_out; d.n_in = y.n_in; d.nnz = (int32_t)nnz; d.pad_ = 0;
+                d.row_ptr = (const int32_t *)(base + q.row_ptr);
+                d.col_idx = (const int32_t *)(base + q.col_idx);
+                d.vals = (float *)(base + q.vals);
+                d.bias = (float *)(base + q.bias);
+                d.t_row_ptr = (const int32_t *)(base + q.t_row_ptr);
+                d.t_row_idx = (const int32_t *)(base + q.t_row_idx);
+                d.t_perm = (const int32_t *)(base + q.t_perm);
+                d.sched = (const int4 *)(base + q.sched);
+                d.t_sched = (const int4 *)(base + q.t_sched);
+                d.X = cfg->training ? (float *)(base + q.X) : nullptr;
+                d.D = cfg->training ? (float *)(base + q.D) : nullptr;
+                d.G[0] = gw ? (float *)(base + q.G[0]) : nullptr;
+                d.G[1] = gw ? (float *)(base + q.G[1]) : nullptr;
+                d.X_prev = !cfg->training ? nullptr
+                           : l == 0       ? (float *)(base + pl.x0)
+                                          : net->layers[l - 1].X;
+                net->max_n = std::max(net->max_n, std::max(y.n_out, y.n_in));
+                net->max_len[0][l] = h.max_len;
+                net->max_len[1][l] = h.t_max_len;
+                UP(d.row_ptr, y.row_ptr, 4 * ((size_t)y.n_out + 1));
+                UP(d.col_idx, y.col_idx, 4 * nnz);
+                UP(d.vals, y.values, 4 * nnz);
+                UP(d.bias, y.bias ? y.bias : zeros.data(), 4 * (size_t)y.n_out);
+                UP(d.t_row_ptr, h.t_row_ptr.data(), 4 * ((size_t)y.n_in + 1));
+                UP(d.t_row_idx, h.t_row_idx.data(), 4 * nnz);
+                UP(d.t_perm, h.t_perm.data(), 4 * nnz);
+                UP(d.sched, h.sched.data(), 16 * (size_t)y.n_out);
+                UP(d.t_sched, h.t_sched.data(), 16 * (size_t)y.n_in);
+            }
+            SYNC(); // the group's host arrays are reused by the next group
+        }
+        net->d_layers = (LayerDev *)(base + pl.table);
+        UP(net->d_layers, net->layers.data(), sizeof(LayerDev) * (size_t)n_layers);
+        SYNC();
+    } catch (...) {
+        return fail_free(fail(nullptr, SDNN_ENOMEM, "host allocation failed during setup"));
     }
-    net->d_layers = (LayerDev *)(base + pl.table);
-    UP(net->d_layers, net->layers.data(), sizeof(LayerDev) * (size_t)n_layers);
 #undef UP
+#undef SYNC
     {
         int devid = 0;
         hipDeviceProp_t prop;
@@ -1175,6 +1410,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
             net->d_n_live[k] = (int32_t *)(base + pl.n_live[k]);
         }
     }
+    if (const char *e = getenv("SDNN_PANEL_COLS")) net->panel_cols = atoi(e);
+    if (const char *e = getenv("SDNN_PANEL_R")) net->panel_r = atoi(e);
     net->bias_nonpos = true;
     for (int32_t l = 1; l < n_layers; ++l)
         if (layers[l].bias)
@@ -1207,6 +1444,13 @@ static int split_v(const sdnn_net *net, int B)
     return B % 512 == 0 ? 4 : B % 256 == 0 ? 2 : 1; // two or more tiles of 64*V samples
 }
 
+// After a failure between fork and join: bring the helper stream back into the caller's stream, so that the
+// caller's stream (or a capture in progress) is not left with a dangling fork.
+static void join_side(sdnn_net *net, hipStream_t stream)
+{
+    if (hipEventRecord(net->ev_join, net->side) == hipSuccess) (void)hipStreamWaitEvent(stream, net->ev_join, 0);
+}
+
 static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Samples per lane for the row-per-wavefront product: as wide as the batch
@@ -1216,6 +1460,46 @@ static int pick_v_spmm(int B, const void *a, const void *b, const void *c)
     if (B % 4 == 0 && B > 128 && aligned(a, 16) && aligned(b, 16) && aligned(c, 16)) return 4;
     if (B % 2 == 0 && B > 64 && aligned(a, 8) && aligned(b, 8) && aligned(c, 8)) return 2;
     return 1;
+}
+
+// The panel sweep (k_spmm_panel) over all 64-sample tiles of the batch; a's operand fields are filled in.
+template <int MODE>
+static int launch_spmm_panel(sdnn_net *net, const LayerDev &d, SpmmArgs a, int B, hipStream_t stream)
+{
+    a.tile_base = 0;
+    a.n_tiles = (uint32_t)((B + 63) / 64);
+    const int n_cols = MODE == 0 ? d.n_in : d.n_out;
+    // rows per wavefront: enough for the wavefronts resident on an XCD to hold all the rows that the XCD
+    // has of one tile, so that the whole tile is swept panel by panel in one go (at most 8)
+    const int xcds = 8;
+    const int64_t rows_per_xcd = a.n_tiles >= 8 ? a.n_rows : (a.n_rows + xcds - 1) / xcds;
+    int ri = 0;
+    for (;; ++ri) {
+        const void *fn_r = ri == 0 ? (const void *)k_spmm_panel<1, MODE> : ri == 1 ? (const void *)k_spmm_panel<2, MODE>
+                           : ri == 2 ? (const void *)k_spmm_panel<4, MODE> : (const void *)k_spmm_panel<8, MODE>;
+        int &occ = net->occ_panel[MODE][ri];
+        if (occ == 0) {
+            HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn_r, BLOCK_THREADS, 0));
+            if (occ < 1) occ = 1;
+        }
+        const int64_t resident = (int64_t)occ * WAVES_PER_BLOCK * (net->n_cu / xcds);
+        if (net->panel_r ? (1 << ri) >= net->panel_r : (resident << ri) >= rows_per_xcd) break;
+        if (ri == 3) break;
+    }
+    const int R = 1 << ri;
+    const void *fn = ri == 0 ? (const void *)k_spmm_panel<1, MODE> : ri == 1 ? (const void *)k_spmm_panel<2, MODE>
+                     : ri == 2 ? (const void *)k_spmm_panel<4, MODE> : (const void *)k_spmm_panel<8, MODE>;
+    a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK * R - 1) / (WAVES_PER_BLOCK * R));
+    const uint64_t blocks = (uint64_t)a.n_tiles * a.n_rg;
+    if (blocks > 0x7fffffffull) return fail(net, SDNN_EINVAL, "grid too large");
+    a.n_vblocks = (uint32_t)blocks;
+    uint64_t g = std::min<uint64_t>(blocks, (uint64_t)net->occ_panel[MODE][ri] * (uint64_t)net->n_cu);
+    if (g >= 8) g &= ~(uint64_t)7;
+    int n_cols_arg = n_cols, panel = net->panel_cols;
+    void *args[] = {(void *)&a, (void *)&n_cols_arg, (void *)&panel};
+    HIP_TRY(net, hipLaunchKernel(fn, dim3((unsigned)g), dim3(BLOCK_THREADS), args, 0, stream));
+    HIP_TRY(net, hipGetLastError());
+    return SDNN_OK;
 }
 
 // part/n_parts: the batch tiles of the launch are the part-th of n_parts equal shares (n_parts = 2
@@ -1254,6 +1538,10 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
             hipLaunchKernelGGL(k_spmv<MODE>, dim3((unsigned)((a.n_rows + 255) / 256)), dim3(256), 0, stream, a);
         HIP_TRY(net, hipGetLastError());
         return SDNN_OK;
+    }
+    if (net->panel_cols > 0 && !n_live && !flags && n_parts == 1 && force_v == 0) {
+        const int l = (int)(&d - net->layers.data());
+        if (net->max_len[MODE][l] <= 64) return launch_spmm_panel<MODE>(net, d, a, B, stream);
     }
     const int V = force_v ? force_v : pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
     const uint32_t all_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
@@ -1299,14 +1587,12 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     return SDNN_OK;
 }
 
-extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream_)
+// Eq. 3 for l = 1..L.  Inference nets stage the activations between the layers in ping / pong
+// (each at least 4 * max_n * B bytes); training nets keep every X_l in the workspace and ignore them.
+static int forward_impl(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream_, float *ping,
+                        float *pong)
 {
-    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
-    if (!d_X0) return fail(net, SDNN_EINVAL, "d_X0 is NULL");
-    if (B < 1 || B > net->cfg.max_batch)
-        return fail(net, SDNN_EINVAL, "B = %d outside 1..max_batch = %d", B, net->cfg.max_batch);
     const bool training = net->cfg.training != 0;
-    if (!training && !d_XL) return fail(net, SDNN_EINVAL, "d_XL is NULL");
     hipStream_t stream = (hipStream_t)stream_;
     net->state = ST_IDLE;
     const int L = net->n_layers;
@@ -1324,11 +1610,14 @@ extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *
     }
     for (int l = 0; l < L; ++l) {
         const LayerDev &d = net->layers[l];
-        float *out = training ? d.X : (l == L - 1 ? d_XL : ((l & 1) ? net->d_pong : net->d_ping));
+        float *out = training ? d.X : (l == L - 1 ? d_XL : ((l & 1) ? pong : ping));
         int rc = sv ? launch_spmm<0>(net, d, in, out, d.bias, B, stream, 0, 2, sv)
                     : launch_spmm<0>(net, d, in, out, d.bias, B, stream);
         if (!rc && sv) rc = launch_spmm<0>(net, d, in, out, d.bias, B, net->side, 1, 2, sv);
-        if (rc) return rc;
+        if (rc) {
+            if (sv) join_side(net, stream);
+            return rc;
+        }
         in = out;
     }
     if (sv) {
@@ -1342,6 +1631,23 @@ extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *
     net->B = B;
     net->state = ST_FORWARD;
     return SDNN_OK;
+}
+
+static int check_forward_args(sdnn_net *net, const float *d_X0, int32_t B, const float *d_XL)
+{
+    if (!net) return fail(nullptr, SDNN_EINVAL, "net is NULL");
+    if (!d_X0) return fail(net, SDNN_EINVAL, "d_X0 is NULL");
+    if (B < 1 || B > net->cfg.max_batch)
+        return fail(net, SDNN_EINVAL, "B = %d outside 1..max_batch = %d", B, net->cfg.max_batch);
+    if (!net->cfg.training && !d_XL) return fail(net, SDNN_EINVAL, "d_XL is NULL");
+    return SDNN_OK;
+}
+
+extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream_)
+{
+    const int rc = check_forward_args(net, d_X0, B, d_XL);
+    if (rc) return rc;
+    return forward_impl(net, d_X0, B, d_XL, stream_, net->d_ping, net->d_pong);
 }
 
 
@@ -1488,7 +1794,10 @@ extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
                     : launch_spmm<1>(net, d, d.D, dprev, d.X_prev, B, stream);
             if (!rc && sv) rc = launch_spmm<1>(net, d, d.D, dprev, d.X_prev, B, net->side, 1, 2, sv);
         }
-        if (rc) return rc;
+        if (rc) {
+            if (sv) join_side(net, stream);
+            return rc;
+        }
     }
     if (sv) {
         HIP_TRY(net, hipEventRecord(net->ev_join, net->side));
@@ -1566,7 +1875,7 @@ extern "C" int sdnn_sgd_step(sdnn_net *net, float lr, void *stream_)
                                    (hipStream_t)stream_, net->d_layers + l0, net->grad_parts, lr);
             if (max_rows > 0 && net->cfg.update_bias)
                 hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((max_rows + 16 * WAVES_PER_BLOCK - 1) / (16 * WAVES_PER_BLOCK)), (unsigned)nl),
-                                   dim3(BLOCK_THREADS), 0, (hipStream_t)stream_, net->d_layers + l0, net->B, lr);
+                                   dim3(BLOCK_THREADS), 0, (hipStream_t)stream_, net->d_layers + l0, net->B, lr, (float *)nullptr);
             HIP_TRY(net, hipGetLastError());
         }
     } else {
@@ -1585,6 +1894,20 @@ extern "C" int sdnn_weight_grad(sdnn_net *net, int32_t layer, float *d_g, float 
         return fail(net, SDNN_ESTATE, "sdnn_weight_grad needs a preceding sdnn_backward");
     if (layer < 1 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
     if (!d_g && !d_gb) return SDNN_OK;
+    if (net->grad_parts > 0) {
+        // the backward sweep has already formed the gradient that sdnn_sgd_step will apply: hand out that one
+        const LayerDev &d = net->layers[layer - 1];
+        hipStream_t stream = (hipStream_t)stream_;
+        if (d_g && d.nnz > 0)
+            hipLaunchKernelGGL(k_sum_parts, dim3((unsigned)std::min(4096, (d.nnz + 2047) / 2048)), dim3(256), 0, stream,
+                               (const float *)d.G[0], net->grad_parts == 2 ? (const float *)d.G[1] : (const float *)nullptr,
+                               d_g, d.nnz);
+        if (d_gb && d.n_out > 0)
+            hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((d.n_out + 16 * WAVES_PER_BLOCK - 1) / (16 * WAVES_PER_BLOCK)), 1u),
+                               dim3(BLOCK_THREADS), 0, stream, net->d_layers + (layer - 1), net->B, 0.0f, d_gb);
+        HIP_TRY(net, hipGetLastError());
+        return SDNN_OK;
+    }
     return launch_update(net, layer - 1, 1, 0.0f, 1, d_g, d_gb, (hipStream_t)stream_);
 }
 

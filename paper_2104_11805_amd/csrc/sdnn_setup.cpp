@@ -62,13 +62,18 @@ extern "C" int sdnn_transpose_pattern(int32_t n_out, int32_t n_in, const int32_t
     std::fill(t_row_ptr, t_row_ptr + n_in + 1, 0);
     for (int32_t p = 0; p < nnz; ++p) t_row_ptr[col_idx[p] + 1]++;
     for (int32_t i = 0; i < n_in; ++i) t_row_ptr[i + 1] += t_row_ptr[i];
-    std::vector<int32_t> cursor(t_row_ptr, t_row_ptr + n_in);
-    for (int32_t j = 0; j < n_out; ++j)
-        for (int32_t p = row_ptr[j]; p < row_ptr[j + 1]; ++p) {
-            const int32_t q = cursor[col_idx[p]]++;
-            t_row_idx[q] = j;
-            t_perm[q] = p;
-        }
+    try {
+        std::vector<int32_t> cursor(t_row_ptr, t_row_ptr + n_in);
+        for (int32_t j = 0; j < n_out; ++j)
+            for (int32_t p = row_ptr[j]; p < row_ptr[j + 1]; ++p) {
+                const int32_t q = cursor[col_idx[p]]++;
+                t_row_idx[q] = j;
+                t_perm[q] = p;
+            }
+    } catch (...) { // nothing may cross the C boundary
+        sdnn_set_global_error("host allocation failed");
+        return SDNN_ENOMEM;
+    }
     return SDNN_OK;
 }
 
@@ -79,9 +84,14 @@ extern "C" int sdnn_row_schedule(int32_t n_rows, const int32_t *row_ptr, int32_t
         return SDNN_EINVAL;
     }
     std::iota(order, order + n_rows, 0);
-    std::stable_sort(order, order + n_rows, [&](int32_t a, int32_t b) {
-        return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
-    });
+    try {
+        std::stable_sort(order, order + n_rows, [&](int32_t a, int32_t b) {
+            return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
+        });
+    } catch (...) {
+        sdnn_set_global_error("host allocation failed");
+        return SDNN_ENOMEM;
+    }
     return SDNN_OK;
 }
 

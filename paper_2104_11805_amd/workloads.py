@@ -20,6 +20,7 @@ Layout conventions used everywhere in this repository:
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
 
@@ -184,8 +185,18 @@ def ragged_layer(seed: int, n_out: int, n_in: int, density: float, n_long_rows: 
 # ----------------------------------------------------------------------------
 
 def binary_inputs(seed: int, n: int, b: int, density: float) -> np.ndarray:
+    """Bernoulli(density) matrix [n][b] of 0.0 / 1.0.  Drawn in row chunks (the generator's stream is
+    consumed in the same order as by one big draw, so the values do not depend on the chunking): the
+    largest input set is 2^29 elements and a single draw would need 4 GB of temporaries."""
     rng = np.random.default_rng(seed)
-    return (rng.random((n, b)) < density).astype(np.float32)
+    out = np.empty((n, b), dtype=np.float32)
+    step = max(1, (1 << 20) // max(b, 1))
+    buf = np.empty((step, b), dtype=np.float64)
+    for r in range(0, n, step):
+        k = min(step, n - r)
+        rng.random(out=buf[:k])
+        np.less(buf[:k], density, out=out[r:r + k], casting="unsafe")
+    return out
 
 
 def mixed_density_inputs(seed: int, n: int, b: int, densities: Sequence[float]) -> np.ndarray:
@@ -214,6 +225,28 @@ def class_labels(seed: int, b: int, n_classes: int) -> np.ndarray:
 # ----------------------------------------------------------------------------
 # the five benchmark configurations (index 1..5) and their "live" companions
 # ----------------------------------------------------------------------------
+
+def _regular_job(job):
+    seed, n, bias = job
+    return regular_layer(seed, n, 32, 0.0625, bias)
+
+
+def _irregular_job(job):
+    seed, n = job
+    return irregular_layer(seed, n)
+
+
+def _build_layers(fn, jobs, threads: bool) -> List[Layer]:
+    """Layers are independent (one seed each), so deep regular nets are drawn by several threads
+    (numpy sorts and draws outside the interpreter lock); the result does not depend on how many.
+    The heavy-tailed layers are drawn one after the other (a per-row Python loop dominates there)."""
+    workers = min(len(jobs), 16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else 4)
+    if not threads or workers <= 1 or len(jobs) < 4:
+        return [fn(j) for j in jobs]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(workers) as ex:
+        return list(ex.map(fn, jobs))
+
 
 #        N      L    bias   B_infer density B_train
 _REGULAR = {
@@ -246,7 +279,7 @@ def make_config(cfg: int, *, n_layers: Optional[int] = None, n: Optional[int] = 
         B = b_infer or B
         Bt = min(b_train or Bt, B)
         dens = dens if density is None else density
-        layers = [regular_layer(1000 * cfg + l, N, 32, 0.0625, bias) for l in range(1, L + 1)]
+        layers = _build_layers(_regular_job, [(1000 * cfg + l, N, bias) for l in range(1, L + 1)], threads=True)
         x = binary_inputs(1000 * cfg + 900, N, B, dens) if with_inputs else np.zeros((N, 0), np.float32)
         tg = uniform_targets(1000 * cfg + 901, N, Bt) if with_inputs else None
         return Workload(f"cfg{cfg}-N{N}-L{L}", layers, 32.0, x, Bt, "mse", 0.01, targets=tg,
@@ -256,7 +289,7 @@ def make_config(cfg: int, *, n_layers: Optional[int] = None, n: Optional[int] = 
         L = n_layers or 30
         B = b_infer or 2048
         Bt = min(b_train or 256, B)
-        layers = [irregular_layer(5000 + l, N) for l in range(1, L + 1)]
+        layers = _build_layers(_irregular_job, [(5000 + l, N) for l in range(1, L + 1)], threads=False)
         x = normal_inputs(5900, N, B) if with_inputs else np.zeros((N, 0), np.float32)
         lab = class_labels(5901, Bt, 10)
         return Workload(f"cfg5-N{N}-L{L}", layers, float("inf"), x, Bt, "softmax_ce", 0.005,

@@ -122,3 +122,67 @@ def compare_step(g, o, what="", exact_fwd=True):
     if exact_fwd:
         assert stats["bitexact_x"] == L + 1, f"{what}: forward not bit-identical to the oracle: {stats}"
     return stats
+
+
+def full_step_compare(work, x0, what="", scale=1.0, log=None):
+    """One training step of a deep, wide net on the GPU and in the oracle, compared layer by layer as
+    the oracle walks Algorithm 1, so that only the oracle's activations (which its backward sweep
+    needs) and its updated weights are ever held on the host.  Same bar as compare_step."""
+    import time
+    t0 = time.time()
+    say = (lambda m: log(f"{what}: {m} [{time.time() - t0:.1f} s]")) if log else (lambda m: None)
+    orc = ORACLES[work.activation]
+    b = x0.shape[1]
+    L = len(work.layers)
+    net = sdnn.Net(work.layers, work.act_cap, b, training=True, activation=work.activation)
+    say(f"net created, workspace {net.workspace_bytes / 2 ** 30:.2f} GiB")
+    xl = torch.empty(work.layers[-1].n_out, b, device=DEV)
+    net.sdnn_forward(dev(x0), xl)
+    dl = gpu_dloss(work, xl, scale)
+    net.sdnn_backward(dl)
+    torch.cuda.synchronize()
+    say("GPU forward + backward done")
+    stats = dict(layers=L, bitexact_x=0, bitexact_d=0, live_x=0, live_d=0, live_g=0, workspace_bytes=net.workspace_bytes)
+    # feed-forward sweep (Eq. 3)
+    xs = [np.ascontiguousarray(x0, dtype=np.float32)]
+    assert np.array_equal(host(net.sdnn_get_activation(0, b)), xs[0])
+    for k in range(1, L + 1):
+        xs.append(orc.forward_layer(work.layers[k - 1], xs[-1], work.act_cap))
+        got = host(net.sdnn_get_activation(k, b))
+        assert_forward_close(got, xs[k], f"{what} X_{k}")
+        stats["bitexact_x"] += int(np.array_equal(got, xs[k]))
+        stats["live_x"] += int((xs[k] != 0).any())
+    say("oracle forward sweep compared")
+    # output delta (Eq. 6), then per layer: gradient (Eq. 4), descent step (Eq. 5), delta of the layer below (Eq. 7)
+    dloss = oracle_dloss_fn(work, scale)(xs[L])
+    assert_grad_close(host(dl), dloss, f"{what} dLoss")
+    delta = orc.output_delta(dloss, xs[L], work.act_cap)
+    new_vals = [None] * L
+    lr = work.lr
+    for k in range(L, 0, -1):
+        got = host(net.sdnn_get_delta(k, b))
+        assert_grad_close(got, delta, f"{what} Delta_{k}")
+        assert np.array_equal(got != 0, delta != 0), f"{what} Delta_{k} support"
+        stats["bitexact_d"] += int(np.array_equal(got, delta))
+        stats["live_d"] += int((delta != 0).any())
+        g, gb = orc.weight_grad(work.layers[k - 1], delta, xs[k - 1])
+        gg, ggb = (host(t) for t in net.sdnn_weight_grad(k))
+        for got_, ref_, name in ((gg, g, "g"), (ggb, gb, "gb")):
+            assert_grad_close(got_, ref_, f"{what} {name}_{k}")
+            if ref_.size and np.abs(ref_).max() > 0:
+                assert_rel_close(got_, ref_, 1e-5, f"{what} {name}_{k} rel")
+        stats["live_g"] += int((g != 0).any())
+        new_vals[k - 1] = (orc.sgd_apply(work.layers[k - 1].values, g, lr), orc.sgd_apply(work.layers[k - 1].bias, gb, lr))
+        if k > 1:
+            delta = orc.backward_layer(work.layers[k - 1], delta, xs[k - 1], work.act_cap)
+        xs[k] = None
+    say("oracle backward sweep and gradients compared")
+    net.sdnn_sgd_step(lr)
+    for k in range(1, L + 1):
+        v, bi = (host(t) for t in net.sdnn_get_weights(k))
+        assert_grad_close(v, new_vals[k - 1][0], f"{what} new values_{k}")
+        assert_grad_close(bi, new_vals[k - 1][1], f"{what} new bias_{k}")
+        new_vals[k - 1] = None
+    net.close()
+    say(f"updated weights compared: {stats}")
+    return stats
