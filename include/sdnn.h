@@ -121,6 +121,20 @@ void sdnn_destroy(sdnn_net *net);
  * In training mode X_0..X_L are kept in the workspace (X_0 is copied). */
 int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream);
 
+/* For callers that cannot allocate device memory at all: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc, and so cannot provide the activation buffers that
+ * sdnn_forward finds in a freshly allocated workspace.  Same computation and same bits as sdnn_forward on
+ * an inference net (training = 0; SDNN_ESTATE otherwise), but the activations between the layers are
+ * staged in a fixed array of SDNN_NOALLOC_SCRATCH_BYTES inside the library's device image (every GPU the
+ * library runs on holds its own copy until the process ends) instead of the workspace's two buffers.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library routine).  Limit: one
+ * activation block must fit half of the array, 4 * (widest layer) * B <= SDNN_NOALLOC_SCRATCH_BYTES / 2,
+ * else SDNN_EINVAL and nothing is launched.  The array keeps the previous call's contents; every element
+ * that a call reads it has written before, so nothing needs clearing.  All calls on one GPU share the
+ * array: calls that overlap on one GPU (different nets, streams or threads) race; order them. */
+#define SDNN_NOALLOC_SCRATCH_BYTES (16u << 20)
+int sdnn_forward_noalloc(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream);
+
 /* The same result as sdnn_forward on an inference net (training = 0), computed without the samples
  * that have died: with the clamped ReLU and biases <= 0, a sample whose activations are all zero
  * after some layer stays zero in every later layer (Eq. 3 with x = 0 gives f(b) = 0), so its column

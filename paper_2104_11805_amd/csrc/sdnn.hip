@@ -29,6 +29,7 @@
 #include <cstring>
 #include <algorithm>
 #include <functional>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -1114,6 +1115,31 @@ extern "C" const char *sdnn_last_error(const sdnn_net *net)
     return net ? net->err : sdnn_global_error();
 }
 
+// Fixed staging array of sdnn_forward_noalloc (the variant of sdnn_forward for callers that cannot
+// allocate): it lives in the library's device image, one copy per GPU, until the process ends.
+static __device__ __align__(256) unsigned char scratch[SDNN_NOALLOC_SCRATCH_BYTES];
+#define MAX_DEVICES 64
+static void *g_scratch_ptr[MAX_DEVICES]; // device address of `scratch` on each GPU, looked up once per GPU
+static std::mutex g_scratch_mutex;
+
+// Address of this GPU's copy of the array (the array's name is only a host-side handle of the
+// symbol: kernels and copies must be given the address that the runtime reports).
+static int scratch_address(sdnn_net *net, void **ptr)
+{
+    int devid = -1;
+    HIP_TRY(net, hipGetDevice(&devid));
+    if (devid < 0 || devid >= MAX_DEVICES) return fail(net, SDNN_EINVAL, "device %d: more GPUs than supported", devid);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[devid]) {
+        void *p = nullptr;
+        HIP_TRY(net, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(net, SDNN_EHIP, "hipGetSymbolAddress returned NULL");
+        g_scratch_ptr[devid] = p;
+    }
+    *ptr = g_scratch_ptr[devid];
+    return SDNN_OK;
+}
+
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace plan: offsets of every array, in one pass (also used to size it).
@@ -1393,6 +1419,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         if (hipGetDevice(&devid) != hipSuccess || hipGetDeviceProperties(&prop, devid) != hipSuccess)
             return fail_free(fail(nullptr, SDNN_EHIP, "cannot query the device"));
         net->n_cu = prop.multiProcessorCount;
+        void *scratch_dev = nullptr; // this GPU's copy of the fixed staging array of sdnn_forward_noalloc
+        if (scratch_address(nullptr, &scratch_dev) != SDNN_OK) return fail_free(SDNN_EHIP);
         // default priority, like every stream here
         if (hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&net->ev_fork, hipEventDisableTiming) != hipSuccess ||
@@ -1648,6 +1676,30 @@ extern "C" int sdnn_forward(sdnn_net *net, const float *d_X0, int32_t B, float *
     const int rc = check_forward_args(net, d_X0, B, d_XL);
     if (rc) return rc;
     return forward_impl(net, d_X0, B, d_XL, stream_, net->d_ping, net->d_pong);
+}
+
+// ---------------------------------------------------------------------------
+// sdnn_forward for callers that cannot allocate: the activations between the layers are staged in
+// a fixed array that lives in the library's device image, one copy per GPU, instead of in two
+// buffers of a caller-allocated workspace.
+// ---------------------------------------------------------------------------
+extern "C" int sdnn_forward_noalloc(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream_)
+{
+    int rc = check_forward_args(net, d_X0, B, d_XL);
+    if (rc) return rc;
+    if (net->cfg.training)
+        return fail(net, SDNN_ESTATE, "sdnn_forward_noalloc is for inference nets (training = 0): a training net "
+                                      "keeps every X_l in its workspace");
+    const size_t half = (size_t)SDNN_NOALLOC_SCRATCH_BYTES / 2;
+    const size_t need = 4 * (size_t)net->max_n * (size_t)B; // one activation buffer, 256-byte aligned by `half`
+    if (need > half)
+        return fail(net, SDNN_EINVAL, "sdnn_forward_noalloc: an activation block of %d neurons x %d samples needs "
+                                      "%zu bytes, the fixed staging array holds %zu per buffer: use a smaller B",
+                    net->max_n, B, need, half);
+    void *base = nullptr;
+    rc = scratch_address(net, &base);
+    if (rc) return rc;
+    return forward_impl(net, d_X0, B, d_XL, stream_, (float *)base, (float *)((char *)base + half));
 }
 
 

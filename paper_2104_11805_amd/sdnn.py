@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsdnn.so")
 SDNN_OK, SDNN_EINVAL, SDNN_ESTATE, SDNN_ENOMEM, SDNN_EHIP = 0, -1, -2, -3, -4
 SDNN_ACT_RELU_CAP, SDNN_ACT_SIGMOID = 0, 1
 SDNN_FUSE_AUTO, SDNN_FUSE_ON, SDNN_FUSE_OFF = 0, 1, -1
+SDNN_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 
 class SdnnError(RuntimeError):
@@ -44,6 +45,7 @@ SIGNATURES = {
     "sdnn_create": (C.c_int, [C.POINTER(sdnn_layer), _I32, C.POINTER(sdnn_config), _P, _SZ, _P, C.POINTER(_P)]),
     "sdnn_destroy": (None, [_P]),
     "sdnn_forward": (C.c_int, [_P, _P, _I32, _P, _P]),
+    "sdnn_forward_noalloc": (C.c_int, [_P, _P, _I32, _P, _P]),
     "sdnn_forward_skip_dead": (C.c_int, [_P, _P, _I32, _P, _I32, _P, _P]),
     "sdnn_backward": (C.c_int, [_P, _P, _P]),
     "sdnn_sgd_step": (C.c_int, [_P, C.c_float, _P]),
@@ -194,6 +196,11 @@ class Net:
     def sdnn_forward(self, x0, xl=None, stream=None):
         b = x0.shape[1]
         _check(lib().sdnn_forward(self._handle, _dp(x0), b, _dp(xl), _stream_ptr(stream)), self._handle)
+        return xl
+
+    def sdnn_forward_noalloc(self, x0, xl, stream=None):
+        b = x0.shape[1]
+        _check(lib().sdnn_forward_noalloc(self._handle, _dp(x0), b, _dp(xl), _stream_ptr(stream)), self._handle)
         return xl
 
     def sdnn_forward_skip_dead(self, x0, xl, check_every: int = 4, n_live=None, stream=None):
