@@ -327,6 +327,12 @@ def main():
     ap.add_argument("--others", type=str, default=None,
                     help="comma-separated configurations for the key other_configs (default: the other four when "
                          "the headline runs at full depth with nominal inputs; 'none' for none)")
+    ap.add_argument("--reorder-study", action="store_true",
+                    help="row order chosen for gather locality (reorder_rows) on and off: a structured topology "
+                         "(rows in groups of 32 share their columns) and the random config-2 pattern")
+    ap.add_argument("--reorder", choices=["both", "0", "1"], default="both",
+                    help="--reorder-study: which settings of reorder_rows to run (one at a time for counter runs)")
+    ap.add_argument("--panel-cols", type=int, default=0, help="sdnn_config.panel_cols for --reorder-study (0 auto, -1 off)")
     ap.add_argument("--time-budget", type=float, default=400.0,
                     help="seconds since program start after which no further other_configs entry is begun")
     args = ap.parse_args()
@@ -343,6 +349,8 @@ def main():
     log("torch and the library are loaded")
     if args.paper_setup:
         return paper_setup_bench(args, np, torch, sdnn, wl)
+    if args.reorder_study:
+        return reorder_study(args, np, torch, sdnn, wl)
 
     head = run_config(args.config, args, args.steps, args.warmup, headline=True)
     if args.others is None:
@@ -435,6 +443,63 @@ def paper_setup_bench(args, np, torch, sdnn, wl):
                                                       "note": "paper Fig. 4, other hardware and the real nets: context only"},
         "cpu_baseline": cpu}))
     net.close()
+
+
+def reorder_study(args, np, torch, sdnn, wl):
+    """Times the training step (minibatch 64) and the inference forward (1024 samples) of two nets with the
+    rows in the default longest-first order and in the clustered order of reorder_rows = 1: a structured
+    topology, where groups of 32 rows share their 32 columns, and the uniformly random pattern of config 2."""
+    dev = "cuda:0"
+    n = args.n if args.n != 1024 else 65536
+    L = args.layers or 12
+    nets = {f"structured (strided links), N={n}, L={L}": [wl.strided_layer(8000 + l, n, value=0.0625, bias=-0.3)
+                                                          for l in range(L)],
+            f"random (config 2 pattern), N=4096, L={4 * L}": wl.make_config(2, n_layers=4 * L, with_inputs=False).layers}
+    out = {}
+    for name, layers in nets.items():
+        N = layers[0].n_in
+        x = torch.from_numpy(wl.binary_inputs(8900, N, 1024, 0.3)).to(dev)
+        xt = x[:, :64].contiguous()
+        y = torch.rand(N, 64, device=dev)
+        res = {}
+        for reorder in ((False, True) if args.reorder == "both" else (args.reorder == "1",)):
+            t0 = time.time()
+            net = sdnn.Net(layers, 32.0, 64, training=True, reorder_rows=reorder, panel_cols=args.panel_cols)
+            torch.cuda.synchronize()
+            create_s = time.time() - t0
+            xl = torch.empty(N, 64, device=dev)
+            dl = torch.empty_like(xl)
+            marks = []
+            for i in range(args.warmup + args.steps):
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                e[0].record(); net.sdnn_forward(xt, xl)
+                e[1].record(); sdnn.sdnn_mse_dloss(xl, y, out=dl); net.sdnn_backward(dl)
+                e[2].record(); net.sdnn_sgd_step(0.0)
+                e[3].record()
+                if i >= args.warmup:
+                    marks.append(e)
+            torch.cuda.synchronize()
+            avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in marks) / len(marks)
+            r = {"step_ms": round(avg(0, 3), 4), "forward_ms": round(avg(0, 1), 4), "backward_ms": round(avg(1, 2), 4),
+                 "update_ms": round(avg(2, 3), 4), "create_s": round(create_s, 2)}
+            net.close()
+            inet = sdnn.Net(layers, 32.0, 1024, training=False, reorder_rows=reorder, panel_cols=args.panel_cols)
+            o = torch.empty(N, 1024, device=dev)
+            inet.sdnn_forward(x, o)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(max(3, args.steps // 2)):
+                inet.sdnn_forward(x, o)
+            torch.cuda.synchronize()
+            r["inference_ms"] = round((time.perf_counter() - t0) * 1e3 / max(3, args.steps // 2), 4)
+            r["checksum"] = float(o.double().sum())
+            inet.close()
+            res["reorder_rows=1" if reorder else "reorder_rows=0"] = r
+        assert len({r["checksum"] for r in res.values()}) == 1
+        out[name] = res
+        log(f"{name}: {res}")
+    print(json.dumps({"study": "row order for gather locality (reorder_rows)", "panel_cols": args.panel_cols, "train_batch": 64, "infer_samples": 1024,
+                      "steps": args.steps, "results": out}))
 
 
 if __name__ == "__main__":

@@ -85,6 +85,8 @@ typedef struct {
     int32_t update_bias; /* 1: sdnn_sgd_step also updates the biases             */
     int32_t activation;  /* SDNN_ACT_RELU_CAP or SDNN_ACT_SIGMOID (act_cap ignored) */
     int32_t fuse_gradient; /* SDNN_FUSE_AUTO / _ON / _OFF, see below               */
+    int32_t panel_cols;  /* SDNN_PANEL_AUTO, SDNN_PANEL_OFF, or a panel width > 0, see below */
+    int32_t reorder_rows; /* 1: order the rows for gather locality at sdnn_create, see below; 0: longest first */
 } sdnn_config;
 
 /* Where the batch allows it (at most 64 samples per launch, short rows), sdnn_backward can form
@@ -96,6 +98,25 @@ typedef struct {
 #define SDNN_FUSE_AUTO 0
 #define SDNN_FUSE_ON 1
 #define SDNN_FUSE_OFF (-1)
+
+/* Wide layers with short rows (at most 64 entries): the products of Eqs. 3 and 7 can sweep their
+ * operand in panels of panel_cols rows, every wavefront carrying several matrix rows through the
+ * panels, so that an L2 holds one panel at a time.  Column indices ascend inside a row, so every sum
+ * keeps its order: same bits.  AUTO (0) uses it where it is faster (operand tiles of 8 MiB and more,
+ * i.e. layers of 32768 neurons and wider); a positive value forces that panel width wherever the
+ * rows are short enough; OFF never uses it. */
+#define SDNN_PANEL_AUTO 0
+#define SDNN_PANEL_OFF (-1)
+
+/* reorder_rows = 1: the order in which the rows of W_l (and of W_l^T) are handed to the wavefronts is chosen
+ * for locality of the gathered operand rows instead of by row length alone: rows that share columns
+ * are clustered (sdnn_cluster_rows) and every cluster is dealt to one XCD, four neighbours to a
+ * workgroup (sdnn_deal_rows_to_xcds), so that an operand row is pulled into one L2 once and reused
+ * there.  This is the single-GPU counterpart of the locality that the paper's partitioned runs gain
+ * (Section 6.3, the discussion of the time breakdown): only the schedule changes, every sum keeps
+ * its order, the results are the same bits.  It pays on structured topologies; on patterns without
+ * shared columns (uniformly random links) nothing is gained. */
+#define SDNN_CLUSTER_ROWS 256 /* largest cluster */
 
 /* ---- setup (Algorithm 1's inputs {W^k}; the paper likewise precomputes its
  *      per-layer index maps once, outside the timed iterations) ------------- */
@@ -197,6 +218,18 @@ int sdnn_transpose_pattern(int32_t n_out, int32_t n_in, const int32_t *row_ptr,
 /* Row schedule: the rows ordered by decreasing number of stored entries (the
  * paper's per-row cost, Section 5), ties by ascending row.  order [n_rows]. */
 int sdnn_row_schedule(int32_t n_rows, const int32_t *row_ptr, int32_t *order);
+
+/* Greedy clustering of the rows of a pattern by shared columns (one pass; a row joins the open cluster
+ * that most of its columns were last used by, if at least a quarter of them were, else it opens a new
+ * one; clusters close at max_cluster_rows).  order [n_rows]: the rows cluster by cluster, clusters by
+ * decreasing longest row, rows inside a cluster by decreasing length.  cluster_of [n_rows] or NULL:
+ * the rank of each row's cluster in that order. */
+int sdnn_cluster_rows(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
+                      int32_t max_cluster_rows, int32_t *order, int32_t *cluster_of);
+/* Deals a row order out to the 8 XCDs: `order` is cut into 8 contiguous stretches of about equal
+ * numbers of entries and stretch x fills the schedule places 32q + 4x .. 32q + 4x + 3, the rows that
+ * run on XCD x (workgroups take 4 consecutive rows; workgroup ids go round the XCDs).  dealt [n_rows]. */
+int sdnn_deal_rows_to_xcds(int32_t n_rows, const int32_t *row_ptr, const int32_t *order, int32_t *dealt);
 
 /* Message of the last failure on this net, or (net == NULL) of the last
  * failure of a call that had no net, on the calling thread. */

@@ -217,7 +217,7 @@ __device__ __forceinline__ RowMeta load_meta(const int4 *sched, const int32_t *i
 // One row of the product for the 64*V samples of one batch tile.  All 64 lanes
 // must be active (lane k's registers are read by readlane); lanes past the end
 // of the batch redo sample 0 and do not store.
-template <int V, int MODE, int U>
+template <int V, int MODE, int U, int ACT>
 __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const float *vals,
                                          const int32_t *perm, const float *in, size_t in_bytes,
                                          float *out, const float *aux, int B, float capf, int act,
@@ -286,7 +286,7 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
     float o[V];
     if (MODE == 0) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) o[v] = act_apply(act, acc[v] + b, capf);
+        for (int v = 0; v < V; ++v) o[v] = act_apply(ACT, acc[v] + b, capf); // compile-time: exp() costs registers
     } else {
 #pragma unroll
         for (int v = 0; v < V; ++v) o[v] = act_backprop(act, acc[v], xp[v], capf);
@@ -303,7 +303,10 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
 // "virtual blocks" blockIdx.x, blockIdx.x + gridDim.x, ...: a wavefront that
 // handles one short row and exits costs more to dispatch than to run.
 // gridDim.x is a multiple of 8, so a workgroup keeps its XCD's tiles.
-template <int V, int MODE, int U, bool TILES_INNER = false>
+// ACT: the activation of the forward epilogue, fixed at compile time (the sigmoid's exp() would
+// otherwise set the register count, and with it the occupancy, of the ReLU kernels too); the
+// backward epilogue reads a.act.
+template <int V, int MODE, int U, bool TILES_INNER, int ACT>
 __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
 {
     const int lane = threadIdx.x & 63;
@@ -321,8 +324,8 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
             if (r >= a.n_rows) continue;
             const RowMeta m = load_meta<MODE>(a.sched, a.idx, a.vals, a.perm, r, lane);
             for (unsigned tile = 0; tile < n_tiles; ++tile)
-                spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act,
-                                     tile + a.tile_base, lane, a.flags);
+                spmm_row<V, MODE, U, ACT>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act,
+                                          tile + a.tile_base, lane, a.flags);
         }
         return;
     }
@@ -332,7 +335,7 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm(const SpmmArgs a)
         const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
         const RowMeta m = load_meta<MODE>(a.sched, a.idx, a.vals, a.perm, r, lane);
-        spmm_row<V, MODE, U>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile + a.tile_base, lane, a.flags);
+        spmm_row<V, MODE, U, ACT>(m, a.idx, a.vals, a.perm, a.in, a.in_bytes, a.out, a.aux, a.B, a.cap, a.act, tile + a.tile_base, lane, a.flags);
     }
 }
 
@@ -385,7 +388,7 @@ __device__ __forceinline__ void panel_consume(float w_l, int k, int ke, const fl
 #undef PANEL_F
 }
 
-template <int R, int MODE>
+template <int R, int MODE, int ACT>
 __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm_panel(const SpmmArgs a, int n_cols, int panel_cols)
 {
     const int lane = threadIdx.x & 63;
@@ -462,7 +465,7 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm_panel(const SpmmArgs a, 
         for (int r = 0; r < R; ++r) {
             if (row[r] < 0) continue;
             float o;
-            if (MODE == 0) o = act_apply(a.act, acc[r] + (a.aux ? (double)a.aux[row[r]] : 0.0), a.cap);
+            if (MODE == 0) o = act_apply(ACT, acc[r] + (a.aux ? (double)a.aux[row[r]] : 0.0), a.cap);
             else o = act_backprop(a.act, acc[r], xp[r], a.cap);
             if (live) a.out[(size_t)row[r] * ld + s] = o;
         }
@@ -1075,11 +1078,11 @@ struct sdnn_net {
     float *d_x0 = nullptr;        // training: X_0 [n_in(1)][max_batch]
     float *d_ping = nullptr, *d_pong = nullptr; // inference: two activation buffers
     int n_cu = 0;                 // compute units of the device
-    int occ_spmm[2][3][2] = {}; // resident workgroups per CU of k_spmm<V,MODE,8,tiles inner>
+    int occ_spmm[2][3][2][2] = {}; // resident workgroups per CU of k_spmm<V,MODE,U,tiles inner>, U = 8, 16
     int occ_grad = 0;             // the same for k_bwd_grad
     int occ_panel[2][4] = {};     // the same for k_spmm_panel<R,MODE>, R = 1, 2, 4, 8
     std::vector<int32_t> max_len[2]; // per layer: longest row of W (0) and of W^T (1)
-    int panel_cols = 0, panel_r = 0; // experiment knobs (environment), 0 = policy
+    std::vector<char> clustered[2];  // per layer: reorder_rows found clusters in W (0), in W^T (1)
     int grad_parts = 0;           // > 0: the last backward pass left the entries' gradient in G[0..grad_parts)
     hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -1162,6 +1165,8 @@ static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_c
         return fail(nullptr, SDNN_EINVAL, "act_cap must be > 0 (or +inf)");
     if (cfg->fuse_gradient < SDNN_FUSE_OFF || cfg->fuse_gradient > SDNN_FUSE_ON)
         return fail(nullptr, SDNN_EINVAL, "unknown fuse_gradient %d", cfg->fuse_gradient);
+    if (cfg->panel_cols < SDNN_PANEL_OFF) return fail(nullptr, SDNN_EINVAL, "panel_cols must be >= -1");
+    if (cfg->reorder_rows != 0 && cfg->reorder_rows != 1) return fail(nullptr, SDNN_EINVAL, "reorder_rows must be 0 or 1");
     for (int32_t l = 0; l < n_layers; ++l) {
         const sdnn_layer &y = layers[l];
         if (y.n_out < 0 || y.n_in < 0 || !y.row_ptr)
@@ -1287,6 +1292,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         net->layers.resize(n_layers);
         net->max_len[0].resize(n_layers);
         net->max_len[1].resize(n_layers);
+        net->clustered[0].resize(n_layers);
+        net->clustered[1].resize(n_layers);
     } catch (...) {
         delete net;
         return fail(nullptr, SDNN_ENOMEM, "host allocation failed");
@@ -1300,6 +1307,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
         std::vector<int4> sched, t_sched;
         int32_t max_len = 0, t_max_len = 0;
+        bool clustered = false, t_clustered = false; // reorder_rows found rows that share columns
         int rc = SDNN_OK;
     };
     auto prepare = [&](int32_t l, HostIdx &h) {
@@ -1316,15 +1324,36 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
             h.rc = sdnn_transpose_pattern(y.n_out, y.n_in, y.row_ptr, y.col_idx, h.t_row_ptr.data(),
                                           h.t_row_idx.data(), h.t_perm.data());
             if (h.rc) return;
-            sdnn_row_schedule(y.n_out, y.row_ptr, h.order.data());
-            sdnn_row_schedule(y.n_in, h.t_row_ptr.data(), h.t_order.data());
+            if (cfg->reorder_rows) {
+                // rows that share columns become neighbours and are dealt to one XCD
+                const size_t n_max = (size_t)std::max(y.n_out, y.n_in);
+                std::vector<int32_t> clustered(n_max), cluster_of(n_max);
+                // "found something": on average at least two rows per cluster
+                auto found = [&](int32_t n) {
+                    int32_t n_clusters = 0;
+                    for (int32_t r = 0; r < n; ++r) n_clusters = std::max(n_clusters, cluster_of[r] + 1);
+                    return 2 * (int64_t)n_clusters <= n;
+                };
+                h.rc = sdnn_cluster_rows(y.n_out, y.n_in, y.row_ptr, y.col_idx, SDNN_CLUSTER_ROWS, clustered.data(),
+                                         cluster_of.data());
+                if (!h.rc) h.clustered = found(y.n_out);
+                if (!h.rc) h.rc = sdnn_deal_rows_to_xcds(y.n_out, y.row_ptr, clustered.data(), h.order.data());
+                if (!h.rc) h.rc = sdnn_cluster_rows(y.n_in, y.n_out, h.t_row_ptr.data(), h.t_row_idx.data(), SDNN_CLUSTER_ROWS,
+                                                    clustered.data(), cluster_of.data());
+                if (!h.rc) h.t_clustered = found(y.n_in);
+                if (!h.rc) h.rc = sdnn_deal_rows_to_xcds(y.n_in, h.t_row_ptr.data(), clustered.data(), h.t_order.data());
+                if (h.rc) return;
+            } else {
+                sdnn_row_schedule(y.n_out, y.row_ptr, h.order.data());
+                sdnn_row_schedule(y.n_in, h.t_row_ptr.data(), h.t_order.data());
+            }
             for (int32_t r = 0; r < y.n_out; ++r)
                 h.sched[r] = make_int4(h.order[r], y.row_ptr[h.order[r]], y.row_ptr[h.order[r] + 1], 0);
             for (int32_t r = 0; r < y.n_in; ++r)
                 h.t_sched[r] = make_int4(h.t_order[r], h.t_row_ptr[h.t_order[r]], h.t_row_ptr[h.t_order[r] + 1], 0);
-            // the schedules list the rows longest first
-            h.max_len = y.n_out > 0 ? h.sched[0].z - h.sched[0].y : 0;
-            h.t_max_len = y.n_in > 0 ? h.t_sched[0].z - h.t_sched[0].y : 0;
+            h.max_len = h.t_max_len = 0;
+            for (int32_t r = 0; r < y.n_out; ++r) h.max_len = std::max(h.max_len, y.row_ptr[r + 1] - y.row_ptr[r]);
+            for (int32_t r = 0; r < y.n_in; ++r) h.t_max_len = std::max(h.t_max_len, h.t_row_ptr[r + 1] - h.t_row_ptr[r]);
         } catch (...) {
             h.rc = SDNN_ENOMEM;
         }
@@ -1393,6 +1422,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 net->max_n = std::max(net->max_n, std::max(y.n_out, y.n_in));
                 net->max_len[0][l] = h.max_len;
                 net->max_len[1][l] = h.t_max_len;
+                net->clustered[0][l] = h.clustered;
+                net->clustered[1][l] = h.t_clustered;
                 UP(d.row_ptr, y.row_ptr, 4 * ((size_t)y.n_out + 1));
                 UP(d.col_idx, y.col_idx, 4 * nnz);
                 UP(d.vals, y.values, 4 * nnz);
@@ -1438,8 +1469,6 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
             net->d_n_live[k] = (int32_t *)(base + pl.n_live[k]);
         }
     }
-    if (const char *e = getenv("SDNN_PANEL_COLS")) net->panel_cols = atoi(e);
-    if (const char *e = getenv("SDNN_PANEL_R")) net->panel_r = atoi(e);
     net->bias_nonpos = true;
     for (int32_t l = 1; l < n_layers; ++l)
         if (layers[l].bias)
@@ -1490,9 +1519,41 @@ static int pick_v_spmm(int B, const void *a, const void *b, const void *c)
     return 1;
 }
 
+// Kernel tables.  The forward kernels are compiled per activation, the backward ones once (ACT = 0).
+template <int MODE, int V, int U, bool TI>
+static const void *spmm_fn_act(int act)
+{
+    if (MODE == 0 && act == ACT_SIGMOID) return (const void *)k_spmm<V, MODE, U, TI, (MODE == 0 ? ACT_SIGMOID : 0)>;
+    return (const void *)k_spmm<V, MODE, U, TI, 0>;
+}
+template <int MODE, int V>
+static const void *spmm_fn_v(int U, bool ti, int act)
+{
+    if (ti) return spmm_fn_act<MODE, V, 8, true>(act);
+    if (U == 16) return spmm_fn_act<MODE, V, 16, false>(act);
+    return spmm_fn_act<MODE, V, 8, false>(act);
+}
+template <int MODE>
+static const void *spmm_fn(int V, int U, bool ti, int act)
+{
+    return V == 4 ? spmm_fn_v<MODE, 4>(U, ti, act) : V == 2 ? spmm_fn_v<MODE, 2>(U, ti, act) : spmm_fn_v<MODE, 1>(U, ti, act);
+}
+template <int MODE, int R>
+static const void *panel_fn_act(int act)
+{
+    if (MODE == 0 && act == ACT_SIGMOID) return (const void *)k_spmm_panel<R, MODE, (MODE == 0 ? ACT_SIGMOID : 0)>;
+    return (const void *)k_spmm_panel<R, MODE, 0>;
+}
+template <int MODE>
+static const void *panel_fn(int ri, int act)
+{
+    return ri == 0 ? panel_fn_act<MODE, 1>(act) : ri == 1 ? panel_fn_act<MODE, 2>(act)
+           : ri == 2 ? panel_fn_act<MODE, 4>(act) : panel_fn_act<MODE, 8>(act);
+}
+
 // The panel sweep (k_spmm_panel) over all 64-sample tiles of the batch; a's operand fields are filled in.
 template <int MODE>
-static int launch_spmm_panel(sdnn_net *net, const LayerDev &d, SpmmArgs a, int B, hipStream_t stream)
+static int launch_spmm_panel(sdnn_net *net, const LayerDev &d, SpmmArgs a, int B, int panel, hipStream_t stream)
 {
     a.tile_base = 0;
     a.n_tiles = (uint32_t)((B + 63) / 64);
@@ -1503,27 +1564,25 @@ static int launch_spmm_panel(sdnn_net *net, const LayerDev &d, SpmmArgs a, int B
     const int64_t rows_per_xcd = a.n_tiles >= 8 ? a.n_rows : (a.n_rows + xcds - 1) / xcds;
     int ri = 0;
     for (;; ++ri) {
-        const void *fn_r = ri == 0 ? (const void *)k_spmm_panel<1, MODE> : ri == 1 ? (const void *)k_spmm_panel<2, MODE>
-                           : ri == 2 ? (const void *)k_spmm_panel<4, MODE> : (const void *)k_spmm_panel<8, MODE>;
+        const void *fn_r = panel_fn<MODE>(ri, net->cfg.activation);
         int &occ = net->occ_panel[MODE][ri];
         if (occ == 0) {
             HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn_r, BLOCK_THREADS, 0));
             if (occ < 1) occ = 1;
         }
         const int64_t resident = (int64_t)occ * WAVES_PER_BLOCK * (net->n_cu / xcds);
-        if (net->panel_r ? (1 << ri) >= net->panel_r : (resident << ri) >= rows_per_xcd) break;
+        if ((resident << ri) >= rows_per_xcd) break;
         if (ri == 3) break;
     }
     const int R = 1 << ri;
-    const void *fn = ri == 0 ? (const void *)k_spmm_panel<1, MODE> : ri == 1 ? (const void *)k_spmm_panel<2, MODE>
-                     : ri == 2 ? (const void *)k_spmm_panel<4, MODE> : (const void *)k_spmm_panel<8, MODE>;
+    const void *fn = panel_fn<MODE>(ri, net->cfg.activation);
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK * R - 1) / (WAVES_PER_BLOCK * R));
     const uint64_t blocks = (uint64_t)a.n_tiles * a.n_rg;
     if (blocks > 0x7fffffffull) return fail(net, SDNN_EINVAL, "grid too large");
     a.n_vblocks = (uint32_t)blocks;
     uint64_t g = std::min<uint64_t>(blocks, (uint64_t)net->occ_panel[MODE][ri] * (uint64_t)net->n_cu);
     if (g >= 8) g &= ~(uint64_t)7;
-    int n_cols_arg = n_cols, panel = net->panel_cols;
+    int n_cols_arg = n_cols;
     void *args[] = {(void *)&a, (void *)&n_cols_arg, (void *)&panel};
     HIP_TRY(net, hipLaunchKernel(fn, dim3((unsigned)g), dim3(BLOCK_THREADS), args, 0, stream));
     HIP_TRY(net, hipGetLastError());
@@ -1567,9 +1626,19 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
         HIP_TRY(net, hipGetLastError());
         return SDNN_OK;
     }
-    if (net->panel_cols > 0 && !n_live && !flags && n_parts == 1 && force_v == 0) {
+    // Wide layers with short rows: when a 64-sample tile of the operand (n_cols x 256 B) is at least twice
+    // the chip's eight L2s, the panel sweep is faster (measured, 65536 columns: forward of a 64-sample
+    // minibatch 64.8 -> 53.6 us per layer, inference in blocks of 1024 samples 217 -> 179 ms per 24 layers;
+    // 16384 columns and fewer: slower than the kernels below).  sdnn_config.panel_cols overrides.
+    if (!n_live && !flags && n_parts == 1 && force_v == 0 && net->cfg.panel_cols >= 0) {
         const int l = (int)(&d - net->layers.data());
-        if (net->max_len[MODE][l] <= 64) return launch_spmm_panel<MODE>(net, d, a, B, stream);
+        const int n_cols = MODE == 0 ? d.n_in : d.n_out;
+        int panel = net->cfg.panel_cols;
+        // (not where reorder_rows has found clusters: their locality comes from the row order, which the
+        // panel kernel's larger workgroups would deal to the XCDs differently: 9.8 vs 6.8 ms on a structured net)
+        if (panel == 0 && (int64_t)n_cols * 256 >= ((int64_t)8 << 20) && d.nnz > 0 && !net->clustered[MODE][l])
+            panel = B > 448 ? 6144 : 8192; // eight or more tiles: every XCD sweeps tiles of its own
+        if (panel > 0 && net->max_len[MODE][l] <= 64) return launch_spmm_panel<MODE>(net, d, a, B, panel, stream);
     }
     const int V = force_v ? force_v : pick_v_spmm(B, in, out, MODE == 1 ? aux : nullptr);
     const uint32_t all_tiles = (uint32_t)((B + 64 * V - 1) / (64 * V));
@@ -1585,23 +1654,14 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     // virtual blocks.  Long, uneven rows (hundreds of entries): 16 in flight and one workgroup per
     // virtual block, so that the hardware hands out the rows, longest first, as wavefronts retire.
     const bool long_rows = (int64_t)d.nnz >= 128 * (int64_t)a.n_rows;
-    const void *fn;
-    if (long_rows)
-        fn = V == 4 ? (const void *)k_spmm<4, MODE, 16> : V == 2 ? (const void *)k_spmm<2, MODE, 16>
-                                                                 : (const void *)k_spmm<1, MODE, 16>;
-    else
-        fn = V == 4 ? (const void *)k_spmm<4, MODE, 8> : V == 2 ? (const void *)k_spmm<2, MODE, 8>
-                                                                : (const void *)k_spmm<1, MODE, 8>;
     uint64_t g = blocks;
     // short rows and a few batch tiles (shared by all XCDs): workgroups are dealt row groups and walk the tiles
     const bool tiles_inner = !long_rows && a.n_tiles >= 2 && a.n_tiles < 8;
-    if (tiles_inner) {
-        g = a.n_rg;
-        fn = V == 4 ? (const void *)k_spmm<4, MODE, 8, true> : V == 2 ? (const void *)k_spmm<2, MODE, 8, true>
-                                                                      : (const void *)k_spmm<1, MODE, 8, true>;
-    }
+    if (tiles_inner) g = a.n_rg;
+    const int U = long_rows ? 16 : 8;
+    const void *fn = spmm_fn<MODE>(V, U, tiles_inner, net->cfg.activation);
     if (!long_rows) {
-        int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0][tiles_inner ? 1 : 0];
+        int &per_cu = net->occ_spmm[MODE][V == 4 ? 2 : V == 2 ? 1 : 0][tiles_inner ? 1 : 0][U == 16 ? 1 : 0];
         if (per_cu == 0) {
             HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BLOCK_THREADS, 0));
             if (per_cu < 1) per_cu = 1;

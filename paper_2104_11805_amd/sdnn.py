@@ -20,6 +20,7 @@ SDNN_OK, SDNN_EINVAL, SDNN_ESTATE, SDNN_ENOMEM, SDNN_EHIP = 0, -1, -2, -3, -4
 SDNN_ACT_RELU_CAP, SDNN_ACT_SIGMOID = 0, 1
 SDNN_FUSE_AUTO, SDNN_FUSE_ON, SDNN_FUSE_OFF = 0, 1, -1
 SDNN_NOALLOC_SCRATCH_BYTES = 16 << 20
+SDNN_PANEL_AUTO, SDNN_PANEL_OFF = 0, -1
 
 
 class SdnnError(RuntimeError):
@@ -35,7 +36,8 @@ class sdnn_layer(C.Structure):
 
 class sdnn_config(C.Structure):
     _fields_ = [("act_cap", C.c_float), ("max_batch", C.c_int32), ("training", C.c_int32),
-                ("update_bias", C.c_int32), ("activation", C.c_int32), ("fuse_gradient", C.c_int32)]
+                ("update_bias", C.c_int32), ("activation", C.c_int32), ("fuse_gradient", C.c_int32),
+                ("panel_cols", C.c_int32), ("reorder_rows", C.c_int32)]
 
 
 # name -> (restype, argtypes); every symbol include/sdnn.h declares
@@ -60,6 +62,8 @@ SIGNATURES = {
     "sdnn_check_csr": (C.c_int, [_I32, _I32, _P, _P]),
     "sdnn_transpose_pattern": (C.c_int, [_I32, _I32, _P, _P, _P, _P, _P]),
     "sdnn_row_schedule": (C.c_int, [_I32, _P, _P]),
+    "sdnn_cluster_rows": (C.c_int, [_I32, _I32, _P, _P, _I32, _P, _P]),
+    "sdnn_deal_rows_to_xcds": (C.c_int, [_I32, _P, _P, _P]),
     "sdnn_last_error": (C.c_char_p, [_P]),
     "sdnn_version": (C.c_char_p, []),
 }
@@ -128,6 +132,21 @@ def sdnn_row_schedule(n_rows, row_ptr):
     return order
 
 
+def sdnn_cluster_rows(n_rows, n_cols, row_ptr, col_idx, max_cluster_rows=256):
+    rp, ci = _np(row_ptr, np.int32), _np(col_idx, np.int32)
+    order = np.empty(n_rows, np.int32)
+    cluster_of = np.empty(n_rows, np.int32)
+    _check(lib().sdnn_cluster_rows(n_rows, n_cols, _hp(rp), _hp(ci), max_cluster_rows, _hp(order), _hp(cluster_of)))
+    return order, cluster_of
+
+
+def sdnn_deal_rows_to_xcds(n_rows, row_ptr, order):
+    rp, od = _np(row_ptr, np.int32), _np(order, np.int32)
+    dealt = np.empty(n_rows, np.int32)
+    _check(lib().sdnn_deal_rows_to_xcds(n_rows, _hp(rp), _hp(od), _hp(dealt)))
+    return dealt
+
+
 # ---- the network handle ------------------------------------------------------
 
 def _stream_ptr(stream=None):
@@ -149,7 +168,7 @@ class Net:
 
     def __init__(self, layers: Sequence, act_cap: float, max_batch: int, training: bool = True,
                  update_bias: bool = True, device: str = "cuda:0", activation: str = "relu",
-                 fuse_gradient: int = 0):
+                 fuse_gradient: int = 0, panel_cols: int = 0, reorder_rows: bool = False):
         import torch
         self._handle = None
         self._keep = []
@@ -163,7 +182,7 @@ class Net:
                                 None if bi is None else _hp(bi).value)
         self.cfg = sdnn_config(float(act_cap), int(max_batch), int(training), int(update_bias),
                                {"relu": SDNN_ACT_RELU_CAP, "sigmoid": SDNN_ACT_SIGMOID}[activation],
-                               int(fuse_gradient))
+                               int(fuse_gradient), int(panel_cols), int(reorder_rows))
         nbytes = C.c_size_t(0)
         _check(lib().sdnn_workspace_bytes(arr, len(layers), C.byref(self.cfg), C.byref(nbytes)))
         self.device = torch.device(device)

@@ -102,6 +102,25 @@ def regular_layer(seed: int, n: int, d: int, value: float, bias: float,
                  np.full(n, bias, dtype=np.float32))
 
 
+def strided_layer(seed: int, n: int, d: int = 32, scale: float = 0.25, bias_scale: float = 0.1,
+                  value: Optional[float] = None, bias: Optional[float] = None) -> Layer:
+    """Structured n x n layer in the manner of the butterfly-like benchmark topologies: neuron j is
+    linked to the d neurons (j + k * n/d) mod n, k = 0..d-1, of the previous layer, so the d rows
+    j, j + n/d, j + 2n/d, ... share one set of d columns while neighbouring rows share none.  Weights
+    normal(0, scale) and biases normal(0, bias_scale) unless constants are given."""
+    if n % d:
+        raise ValueError("n must be a multiple of d")
+    rng = np.random.default_rng(seed)
+    stride = n // d
+    cols = (np.arange(n, dtype=np.int64)[:, None] + stride * np.arange(d, dtype=np.int64)[None, :]) % n
+    cols = np.sort(cols, axis=1).astype(np.int32)
+    row_ptr = (np.arange(n + 1, dtype=np.int64) * d).astype(np.int32)
+    values = (np.full(n * d, value, np.float32) if value is not None
+              else (rng.standard_normal(n * d) * scale).astype(np.float32))
+    b = (np.full(n, bias, np.float32) if bias is not None else (rng.standard_normal(n) * bias_scale).astype(np.float32))
+    return Layer(n, n, row_ptr, cols.reshape(-1), values, b)
+
+
 def heavy_tail_degrees(rng: np.random.Generator, n: int, s: float, cap: int, mean: float) -> np.ndarray:
     """Row degrees deg_i = clip(round(c * Z_i), 1, cap) with Z_i ~ Zipf(s).
 

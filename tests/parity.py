@@ -43,11 +43,12 @@ def gpu_dloss(work, xl, scale=1.0):
     return d
 
 
-def gpu_train_step(work, x0, lr=None, scale=1.0, update_bias=True, max_batch=None, keep=True, fuse_gradient=0):
+def gpu_train_step(work, x0, lr=None, scale=1.0, update_bias=True, max_batch=None, keep=True, fuse_gradient=0,
+                   **net_options):
     """forward + backward + sgd_step through the C ABI; returns everything as numpy."""
     b = x0.shape[1]
     net = sdnn.Net(work.layers, work.act_cap, max_batch or b, training=True, update_bias=update_bias,
-                   activation=work.activation, fuse_gradient=fuse_gradient)
+                   activation=work.activation, fuse_gradient=fuse_gradient, **net_options)
     L = net.n_layers
     xl = torch.empty(work.layers[-1].n_out, b, device=DEV)
     net.sdnn_forward(dev(x0), xl)

@@ -1,0 +1,100 @@
+"""Options that change how the work is laid out on the chip, never what is computed: the row order
+chosen for gather locality (reorder_rows) and the column-panel sweep of wide layers (panel_cols).
+Every result must be the bits of the oracle (forward, deltas) or within the usual bar (gradients)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2104_11805_amd import sdnn, workloads as wl
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _work(layers, b, seed, cap=1.5, inputs="normal"):
+    n_in, n_out = layers[0].n_in, layers[-1].n_out
+    x = wl.normal_inputs(seed, n_in, b) if inputs == "normal" else wl.binary_inputs(seed, n_in, b, 0.4)
+    return wl.Workload("layout", layers, cap, x, b, "mse", 0.05, targets=wl.uniform_targets(seed + 1, n_out, b))
+
+
+@pytest.mark.parametrize("b,fuse", [(64, 0), (64, 1), (128, 1), (300, 0), (1, 0)])
+def test_reordered_rows_structured_net(b, fuse):
+    """Butterfly-like pattern (32 rows share each column set): the clustered schedule gives the oracle's result."""
+    layers = [wl.strided_layer(600 + l, 2048) for l in range(4)]
+    work = _work(layers, b, 610)
+    g = P.gpu_train_step(work, work.x_train, fuse_gradient=fuse, reorder_rows=True)
+    o = P.oracle_train_step(work, work.x_train)
+    st = P.compare_step(g, o, f"reordered strided b={b} fuse={fuse}")
+    assert st["live_g"] == 4
+    plain = P.gpu_train_step(work, work.x_train, fuse_gradient=fuse, reorder_rows=False)
+    for k in range(5):
+        assert np.array_equal(g["xs"][k], plain["xs"][k])
+    for k in range(1, 5):
+        assert np.array_equal(g["deltas"][k], plain["deltas"][k])
+        assert np.array_equal(g["new"][k - 1][0], plain["new"][k - 1][0])
+
+
+def test_reordered_rows_irregular_and_random_nets():
+    work = wl.make_config(5, n=1024, n_layers=3, b_infer=96, b_train=96)
+    g = P.gpu_train_step(work, work.x_train, scale=4096.0, reorder_rows=True)
+    o = P.oracle_train_step(work, work.x_train, scale=4096.0)
+    P.compare_step(g, o, "reordered irregular")
+    work = wl.make_config(1, n_layers=6, density=0.40)
+    g = P.gpu_train_step(work, work.x_train, reorder_rows=True)
+    o = P.oracle_train_step(work, work.x_train)
+    assert P.compare_step(g, o, "reordered cfg1")["live_g"] == 6
+    layers = [wl.ragged_layer(40 + l, 500, 500, 0.01, 3, 300, 3, 200) for l in range(2)]   # long rows, empty rows
+    work = _work(layers, 70, 45, cap=float("inf"))
+    g = P.gpu_train_step(work, work.x_train, reorder_rows=True)
+    o = P.oracle_train_step(work, work.x_train)
+    P.compare_step(g, o, "reordered ragged")
+
+
+def test_reordered_rows_inference_and_skip_dead():
+    layers = [wl.strided_layer(700 + l, 1024, value=0.0625, bias=-0.3) for l in range(8)]
+    x = wl.mixed_density_inputs(705, 1024, 200, (0.05, 0.30, 0.45))
+    ref = P.O32.forward(layers, x, 32.0)[-1]
+    net = sdnn.Net(layers, 32.0, 200, training=False, reorder_rows=True)
+    out = torch.empty(1024, 200, device=P.DEV)
+    net.sdnn_forward(P.dev(x), out)
+    assert np.array_equal(P.host(out), ref)
+    out2 = torch.full((1024, 200), -1.0, device=P.DEV)
+    net.sdnn_forward_skip_dead(P.dev(x), out2, check_every=2)
+    assert np.array_equal(P.host(out2), ref)
+    net.close()
+
+
+@pytest.mark.parametrize("b,cols,n", [(37, 7, 333), (64, 50, 333), (100, 1000, 333), (130, 16, 333), (520, 100, 5000)])
+def test_panel_sweep_forced_on_small_nets(b, cols, n):
+    """panel_cols forced: many narrow panels, ragged rows (some empty), partial last tile; the last case has
+    eight or more tiles, so every XCD sweeps its own tiles with several rows per wavefront."""
+    sizes = (150, n, 97, 210)
+    dens = (0.12, 0.12 if n < 1000 else 0.006, 0.12)
+    layers = [wl.random_layer(900 + l, sizes[l + 1], sizes[l], dens[l], scale=0.5) for l in range(3)]
+    assert max(int(np.diff(l.row_ptr).max()) for l in layers) <= 64
+    work = _work(layers, b, 77, cap=1.2)
+    g = P.gpu_train_step(work, work.x_train, fuse_gradient=-1, panel_cols=cols)
+    o = P.oracle_train_step(work, work.x_train)
+    assert P.compare_step(g, o, f"panel b={b} cols={cols}")["live_g"] == 3
+    net = sdnn.Net(layers, 1.2, b, training=False, panel_cols=cols)
+    out = torch.empty(sizes[-1], b, device=P.DEV)
+    net.sdnn_forward(P.dev(work.x_train), out)
+    assert np.array_equal(P.host(out), o["xs"][-1])
+    net.close()
+
+
+def test_panel_sweep_by_policy_on_a_wide_layer_and_long_rows_fall_back():
+    """65536 columns: the policy sweeps in panels (forward and the separate backward product; rows per
+    wavefront chosen from the row count); a layer with a row of more than 64 entries does not."""
+    work = wl.make_config(4, n_layers=3, density=0.60, b_infer=64, b_train=64)
+    for opts in (dict(fuse_gradient=-1), dict(fuse_gradient=-1, panel_cols=-1), dict(fuse_gradient=-1, reorder_rows=True)):
+        g = P.gpu_train_step(work, work.x_train, **opts)
+        if "o" not in locals():
+            o = P.oracle_train_step(work, work.x_train)
+        assert P.compare_step(g, o, f"cfg4 {opts}")["live_g"] == 3
+    layers = [wl.ragged_layer(50 + l, 400, 400, 0.02, 2, 100, 2, 90) for l in range(2)]
+    assert max(int(np.diff(l.row_ptr).max()) for l in layers) > 64
+    work = _work(layers, 64, 55, cap=float("inf"))
+    g = P.gpu_train_step(work, work.x_train, fuse_gradient=-1, panel_cols=32)
+    o = P.oracle_train_step(work, work.x_train)
+    P.compare_step(g, o, "panel refused for long rows")

@@ -194,3 +194,38 @@ def test_header_is_plain_c_and_host_entry_points_link(tmp_path):
                     "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
     assert "c abi ok" in out
+
+
+def test_row_clustering_finds_planted_clusters_and_deals_them_to_one_xcd():
+    """Structured pattern (rows j, j + n/32, ... share their 32 columns): the greedy clustering recovers exactly
+    those groups; the dealing puts each on one XCD's schedule places; random patterns stay in length order."""
+    n = 2048
+    lay = wl.strided_layer(3, n)
+    order, cl = sdnn.sdnn_cluster_rows(n, n, lay.row_ptr, lay.col_idx)
+    assert sorted(order.tolist()) == list(range(n))
+    assert cl.max() + 1 == n // 32 and (np.bincount(cl) == 32).all()
+    stride = n // 32
+    for c in range(cl.max() + 1):
+        assert len(set((np.nonzero(cl == c)[0] % stride).tolist())) == 1
+    assert (np.diff(cl[order]) >= 0).all()                       # cluster by cluster
+    dealt = sdnn.sdnn_deal_rows_to_xcds(n, lay.row_ptr, order)
+    assert sorted(dealt.tolist()) == list(range(n))
+    xcd_of_row = np.empty(n, int)
+    xcd_of_row[dealt] = (np.arange(n) // 4) % 8
+    assert all(len(set(xcd_of_row[cl == c].tolist())) == 1 for c in range(cl.max() + 1))
+    # capped clusters
+    order2, cl2 = sdnn.sdnn_cluster_rows(n, n, lay.row_ptr, lay.col_idx, 8)
+    assert np.bincount(cl2).max() <= 8 and sorted(order2.tolist()) == list(range(n))
+    # nothing shared: every row its own cluster, the order is the longest-first schedule
+    rnd = wl.regular_layer(2001, 1024, 32, 0.0625, -0.3)
+    order3, cl3 = sdnn.sdnn_cluster_rows(1024, 1024, rnd.row_ptr, rnd.col_idx)
+    assert cl3.max() + 1 == 1024 and np.array_equal(order3, sdnn.sdnn_row_schedule(1024, rnd.row_ptr))
+    irr = wl.irregular_layer(5, 512)
+    order4, _ = sdnn.sdnn_cluster_rows(512, 512, irr.row_ptr, irr.col_idx)
+    dealt4 = sdnn.sdnn_deal_rows_to_xcds(512, irr.row_ptr, order4)
+    assert sorted(order4.tolist()) == list(range(512)) and sorted(dealt4.tolist()) == list(range(512))
+    # degenerate sizes and errors
+    e_order, _ = sdnn.sdnn_cluster_rows(0, 5, np.zeros(1, np.int32), np.zeros(0, np.int32))
+    assert e_order.size == 0
+    assert sdnn.lib().sdnn_cluster_rows(4, 4, None, None, 8, None, None) == sdnn.SDNN_EINVAL
+    assert sdnn.lib().sdnn_deal_rows_to_xcds(4, None, None, None) == sdnn.SDNN_EINVAL
