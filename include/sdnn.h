@@ -87,6 +87,7 @@ typedef struct {
     int32_t fuse_gradient; /* SDNN_FUSE_AUTO / _ON / _OFF, see below               */
     int32_t panel_cols;  /* SDNN_PANEL_AUTO, SDNN_PANEL_OFF, or a panel width > 0, see below */
     int32_t reorder_rows; /* 1: order the rows for gather locality at sdnn_create, see below; 0: longest first */
+    int32_t lds_forward; /* SDNN_LDS_AUTO / _ON / _OFF, see below                  */
 } sdnn_config;
 
 /* Where the batch allows it (at most 64 samples per launch, short rows), sdnn_backward can form
@@ -117,6 +118,18 @@ typedef struct {
  * its order, the results are the same bits.  It pays on structured topologies; on patterns without
  * shared columns (uniformly random links) nothing is gained. */
 #define SDNN_CLUSTER_ROWS 256 /* largest cluster */
+
+/* Inference nets (training = 0) whose widest layer has at most 4096 neurons can run sdnn_forward as ONE
+ * launch in which a workgroup carries 4 samples through all layers with their activations held in
+ * LDS (the samples are independent, Section 5.1, so nothing is exchanged between workgroups); the
+ * weights are streamed from a second, lane-major copy that sdnn_create builds (8 more bytes of
+ * workspace per stored entry; sdnn_set_weights keeps it current).  Every row still adds its terms
+ * in storage order: same bits as the per-layer kernels.  AUTO builds the copy and uses the launch
+ * where it is faster (enough samples to fill the chip, or layers so small that per-layer launches
+ * are bound by their latency); ON uses it whenever the copy exists; OFF never builds it. */
+#define SDNN_LDS_AUTO 0
+#define SDNN_LDS_ON 1
+#define SDNN_LDS_OFF (-1)
 
 /* ---- setup (Algorithm 1's inputs {W^k}; the paper likewise precomputes its
  *      per-layer index maps once, outside the timed iterations) ------------- */

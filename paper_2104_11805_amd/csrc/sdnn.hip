@@ -40,6 +40,8 @@
 // device helpers
 // ---------------------------------------------------------------------------
 
+#define LDS_T 4        // samples a workgroup of the LDS-resident forward carries
+#define LDS_MAX_N 4096 // its widest layer: 2 buffers x 4096 x 4 samples x 4 B = 128 KiB of the CU's 160 KiB
 #define WAVES_PER_BLOCK 4 // product kernels: 4 rows per workgroup (measured best of 1, 2, 4, 8)
 #define UPD_WAVES 1       // update kernel: one wavefront per workgroup (measured best of 1, 2, 4, 8)
 #define BLOCK_THREADS (64 * WAVES_PER_BLOCK)
@@ -470,6 +472,149 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_spmm_panel(const SpmmArgs a, 
             if (live) a.out[(size_t)row[r] * ld + s] = o;
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// K1f: the whole feed-forward sweep (Eq. 3 for l = 1..L) in one launch, for nets whose widest layer
+// fits in LDS.  The batch vectors are independent (they are the columns of X, Section 5.1), so a
+// workgroup takes LDS_T of them through all layers by itself: their activations live in two LDS
+// buffers ([neuron][LDS_T] floats, one read and one written per layer, a workgroup barrier between
+// layers), and only W is streamed, from its lane-major copy: lane r of a wavefront walks row r of a
+// block of 64 rows, one coalesced 8-byte load per entry, one 16-byte LDS read for the LDS_T
+// activations the entry points at.  Every lane adds its row's terms in storage order in fp64: the
+// same sums as k_spmm.  Slots past the end of a row that is shorter than its block hold weight 0
+// and add an exact zero.
+// ---------------------------------------------------------------------------
+#define LDS_WAVES 16 // wavefronts per workgroup: one workgroup per CU
+#define LDS_U 8      // entries in flight per lane
+#define LDS_BLOCKS (LDS_MAX_N / 64 / LDS_WAVES) // blocks of 64 rows a wavefront has per layer, at most
+template <int ACT>
+__global__ void __launch_bounds__(64 * LDS_WAVES)
+k_fwd_lds(const LayerDev *__restrict__ layers, int n_layers, const float *__restrict__ X0, float *__restrict__ XL,
+          int B, int buf_floats, float cap, int vec_io)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds_act[];
+    float *in = lds_act, *out = lds_act + buf_floats;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s0 = blockIdx.x * LDS_T;
+    const bool full = s0 + LDS_T <= B && vec_io; // all LDS_T samples exist and rows of X are 16-byte aligned
+
+    // X_0: the workgroup's LDS_T columns (zeros past the end of the batch)
+    const int n0 = layers[0].n_in;
+    for (int i = tid; i < n0; i += 64 * LDS_WAVES) {
+        const float *src = X0 + (size_t)i * B + s0;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (full) {
+            v = *reinterpret_cast<const float4 *>(src);
+        } else {
+            if (s0 + 0 < B) v.x = src[0];
+            if (s0 + 1 < B) v.y = src[1];
+            if (s0 + 2 < B) v.z = src[2];
+            if (s0 + 3 < B) v.w = src[3];
+        }
+        *reinterpret_cast<float4 *>(in + LDS_T * i) = v;
+    }
+    __syncthreads();
+
+    // A wavefront takes the blocks wave, wave + LDS_WAVES, ... of every layer: at most LDS_BLOCKS of them.  Where
+    // they lie, their rows and biases do not depend on the activations, so all of it is requested at once, a layer
+    // ahead: a layer then starts with its first entries, not with a chain of dependent loads per block.
+    int off_n[LDS_BLOCKS], end_n[LDS_BLOCKS], row_n[LDS_BLOCKS];
+    float bias_n[LDS_BLOCKS];
+    auto request_meta = [&](int l) {
+        const LayerDev &L = layers[l];
+#pragma unroll
+        for (int j = 0; j < LDS_BLOCKS; ++j) {
+            const int b = wave + LDS_WAVES * j;
+            off_n[j] = end_n[j] = 0;
+            row_n[j] = -1;
+            bias_n[j] = 0.0f;
+            if (b < L.n_blocks) {
+                off_n[j] = L.lm_off[b];
+                end_n[j] = L.lm_off[b + 1];
+                row_n[j] = L.lm_row[b * 64 + lane];
+                bias_n[j] = L.lm_bias[b * 64 + lane];
+            }
+        }
+    };
+    request_meta(0);
+    for (int l = 0; l < n_layers; ++l) {
+        const LayerDev &L = layers[l];
+        const bool last = l == n_layers - 1;
+        int off_c[LDS_BLOCKS], end_c[LDS_BLOCKS], row_c[LDS_BLOCKS];
+        float bias_c[LDS_BLOCKS];
+#pragma unroll
+        for (int j = 0; j < LDS_BLOCKS; ++j) { off_c[j] = off_n[j]; end_c[j] = end_n[j]; row_c[j] = row_n[j]; bias_c[j] = bias_n[j]; }
+        if (!last) request_meta(l + 1);
+#pragma unroll
+        for (int j = 0; j < LDS_BLOCKS; ++j) {
+            if (wave + LDS_WAVES * j >= L.n_blocks) break;
+            const int off = off_c[j];
+            const int K = (end_c[j] - off) >> 6; // entries of the block's longest row
+            const int row = row_c[j];
+            const float bias = bias_c[j];
+            const int2 *__restrict__ e = L.lm + off + lane;
+            double acc[LDS_T];
+#pragma unroll
+            for (int t = 0; t < LDS_T; ++t) acc[t] = 0.0;
+            for (int k0 = 0; k0 < K; k0 += LDS_U) {
+                int2 ent[LDS_U];
+                float4 x[LDS_U];
+                if (k0 + LDS_U <= K) {
+#pragma unroll
+                    for (int u = 0; u < LDS_U; ++u) ent[u] = e[(k0 + u) * 64];
+                } else { // the block's last entries: the slots past them add an exact zero
+#pragma unroll
+                    for (int u = 0; u < LDS_U; ++u) ent[u] = k0 + u < K ? e[(k0 + u) * 64] : make_int2(0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < LDS_U; ++u) x[u] = *reinterpret_cast<const float4 *>(in + LDS_T * ent[u].x);
+#pragma unroll
+                for (int u = 0; u < LDS_U; ++u) {
+                    const double w = (double)__int_as_float(ent[u].y);
+                    acc[0] = fma(w, (double)x[u].x, acc[0]);
+                    acc[1] = fma(w, (double)x[u].y, acc[1]);
+                    acc[2] = fma(w, (double)x[u].z, acc[2]);
+                    acc[3] = fma(w, (double)x[u].w, acc[3]);
+                }
+            }
+            if (row >= 0) {
+                const double bd = (double)bias;
+                const float4 o = make_float4(act_apply(ACT, acc[0] + bd, cap), act_apply(ACT, acc[1] + bd, cap),
+                                             act_apply(ACT, acc[2] + bd, cap), act_apply(ACT, acc[3] + bd, cap));
+                if (!last) {
+                    *reinterpret_cast<float4 *>(out + LDS_T * row) = o;
+                } else {
+                    float *dst = XL + (size_t)row * B + s0;
+                    if (full) {
+                        *reinterpret_cast<float4 *>(dst) = o;
+                    } else {
+                        if (s0 + 0 < B) dst[0] = o.x;
+                        if (s0 + 1 < B) dst[1] = o.y;
+                        if (s0 + 2 < B) dst[2] = o.z;
+                        if (s0 + 3 < B) dst[3] = o.w;
+                    }
+                }
+            }
+        }
+        __syncthreads(); // the layer is complete before anyone reads it, and read before it is overwritten
+        float *t = in; in = out; out = t;
+    }
+}
+
+// Rewrites the weights and biases of a layer's lane-major copy from the CSR values and the bias array
+// (after sdnn_set_weights).
+__global__ void __launch_bounds__(64) k_lm_refresh(const LayerDev *__restrict__ layer)
+{
+    const LayerDev &L = *layer;
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int row = L.lm_row[b * 64 + lane];
+    if (row < 0) return;
+    const int off = L.lm_off[b];
+    const int beg = L.row_ptr[row], len = L.row_ptr[row + 1] - beg;
+    for (int k = 0; k < len; ++k) L.lm[off + 64 * k + lane].y = __float_as_int(L.vals[beg + k]);
+    L.lm_bias[b * 64 + lane] = L.bias[row];
 }
 
 // ---------------------------------------------------------------------------
@@ -1083,6 +1228,8 @@ struct sdnn_net {
     int occ_panel[2][4] = {};     // the same for k_spmm_panel<R,MODE>, R = 1, 2, 4, 8
     std::vector<int32_t> max_len[2]; // per layer: longest row of W (0) and of W^T (1)
     std::vector<char> clustered[2];  // per layer: reorder_rows found clusters in W (0), in W^T (1)
+    bool lds_ready = false;          // every layer has its lane-major copy (k_fwd_lds can run)
+    bool lds_attr_set = false;       // the kernels' dynamic LDS limit has been raised
     int grad_parts = 0;           // > 0: the last backward pass left the entries' gradient in G[0..grad_parts)
     hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -1149,6 +1296,7 @@ static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 struct Plan {
     struct PerLayer {
         size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2];
+        size_t lm, lm_off, lm_row, lm_bias, lm_entries, lm_blocks;
     };
     std::vector<PerLayer> pl;
     size_t table = 0, x0 = 0, ping = 0, pong = 0, flags[2] = {0, 0}, map[2] = {0, 0}, n_live[2] = {0, 0}, total = 0;
@@ -1167,6 +1315,8 @@ static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_c
         return fail(nullptr, SDNN_EINVAL, "unknown fuse_gradient %d", cfg->fuse_gradient);
     if (cfg->panel_cols < SDNN_PANEL_OFF) return fail(nullptr, SDNN_EINVAL, "panel_cols must be >= -1");
     if (cfg->reorder_rows != 0 && cfg->reorder_rows != 1) return fail(nullptr, SDNN_EINVAL, "reorder_rows must be 0 or 1");
+    if (cfg->lds_forward < SDNN_LDS_OFF || cfg->lds_forward > SDNN_LDS_ON)
+        return fail(nullptr, SDNN_EINVAL, "unknown lds_forward %d", cfg->lds_forward);
     for (int32_t l = 0; l < n_layers; ++l) {
         const sdnn_layer &y = layers[l];
         if (y.n_out < 0 || y.n_in < 0 || !y.row_ptr)
@@ -1190,6 +1340,28 @@ static bool grad_buffers_wanted(const sdnn_layer *layers, int32_t n_layers, cons
     int64_t rows = 0;
     for (int32_t l = 0; l < n_layers; ++l) rows += layers[l].n_out;
     return rows >= (int64_t)16384 * n_layers;
+}
+
+// The LDS-resident forward (k_fwd_lds) carries LDS_T samples through all layers with two activation
+// buffers of (widest layer) x LDS_T floats in LDS; it is set up for inference nets whose widest
+// layer fits.
+static bool lds_forward_wanted(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg)
+{
+    if (cfg->training || cfg->lds_forward == SDNN_LDS_OFF) return false;
+    for (int32_t l = 0; l < n_layers; ++l)
+        if (layers[l].n_out > LDS_MAX_N || layers[l].n_in > LDS_MAX_N) return false;
+    return true;
+}
+
+// Row lengths, longest first: block b of the lane-major copy is as deep as its first row.
+static size_t lm_padded_entries(const sdnn_layer &y, std::vector<int32_t> &lens)
+{
+    lens.resize((size_t)y.n_out);
+    for (int32_t r = 0; r < y.n_out; ++r) lens[r] = y.row_ptr[r + 1] - y.row_ptr[r];
+    std::sort(lens.begin(), lens.end(), std::greater<int32_t>());
+    size_t total = 0;
+    for (int32_t r = 0; r < y.n_out; r += 64) total += 64 * (size_t)lens[r];
+    return total;
 }
 
 static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg, Plan &pl)
@@ -1221,6 +1393,16 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
                 q.G[0] = take(4 * nnz);
                 q.G[1] = take(4 * nnz);
             }
+        }
+        q.lm = q.lm_off = q.lm_row = q.lm_bias = q.lm_entries = q.lm_blocks = 0;
+        if (lds_forward_wanted(layers, n_layers, cfg)) {
+            std::vector<int32_t> lens;
+            q.lm_entries = lm_padded_entries(y, lens);
+            q.lm_blocks = ((size_t)y.n_out + 63) / 64;
+            q.lm = take(8 * q.lm_entries);
+            q.lm_off = take(4 * (q.lm_blocks + 1));
+            q.lm_row = take(4 * 64 * q.lm_blocks);
+            q.lm_bias = take(4 * 64 * q.lm_blocks);
         }
         max_n = std::max(max_n, (size_t)std::max(y.n_out, y.n_in));
     }
@@ -1306,10 +1488,14 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     struct HostIdx {
         std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
         std::vector<int4> sched, t_sched;
+        std::vector<int2> lm;
+        std::vector<int32_t> lm_off, lm_row;
+        std::vector<float> lm_bias;
         int32_t max_len = 0, t_max_len = 0;
         bool clustered = false, t_clustered = false; // reorder_rows found rows that share columns
         int rc = SDNN_OK;
     };
+    const bool want_lm = lds_forward_wanted(layers, n_layers, cfg);
     auto prepare = [&](int32_t l, HostIdx &h) {
         try {
             const sdnn_layer &y = layers[l];
@@ -1351,6 +1537,31 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 h.sched[r] = make_int4(h.order[r], y.row_ptr[h.order[r]], y.row_ptr[h.order[r] + 1], 0);
             for (int32_t r = 0; r < y.n_in; ++r)
                 h.t_sched[r] = make_int4(h.t_order[r], h.t_row_ptr[h.t_order[r]], h.t_row_ptr[h.t_order[r] + 1], 0);
+            if (want_lm) {
+                // lane-major copy: always in longest-first order, whatever the row schedule is
+                std::vector<int32_t> by_len((size_t)y.n_out);
+                sdnn_row_schedule(y.n_out, y.row_ptr, by_len.data());
+                const int32_t nb = (y.n_out + 63) / 64;
+                h.lm_off.assign((size_t)nb + 1, 0);
+                h.lm_row.assign((size_t)nb * 64, -1);
+                h.lm_bias.assign((size_t)nb * 64, 0.0f);
+                for (int32_t b = 0; b < nb; ++b) {
+                    const int32_t first = by_len[(size_t)b * 64];
+                    h.lm_off[b + 1] = h.lm_off[b] + 64 * (y.row_ptr[first + 1] - y.row_ptr[first]);
+                }
+                h.lm.assign((size_t)h.lm_off[nb], make_int2(0, 0)); // padding: column 0, weight +0.0
+                for (int32_t b = 0; b < nb; ++b)
+                    for (int32_t lane = 0; lane < 64 && b * 64 + lane < y.n_out; ++lane) {
+                        const int32_t row = by_len[(size_t)b * 64 + lane];
+                        h.lm_row[(size_t)b * 64 + lane] = row;
+                        if (y.bias) h.lm_bias[(size_t)b * 64 + lane] = y.bias[row];
+                        for (int32_t p = y.row_ptr[row]; p < y.row_ptr[row + 1]; ++p) {
+                            int32_t bits;
+                            memcpy(&bits, &y.values[p], 4);
+                            h.lm[(size_t)h.lm_off[b] + 64 * (size_t)(p - y.row_ptr[row]) + lane] = make_int2(y.col_idx[p], bits);
+                        }
+                    }
+            }
             h.max_len = h.t_max_len = 0;
             for (int32_t r = 0; r < y.n_out; ++r) h.max_len = std::max(h.max_len, y.row_ptr[r + 1] - y.row_ptr[r]);
             for (int32_t r = 0; r < y.n_in; ++r) h.t_max_len = std::max(h.t_max_len, h.t_row_ptr[r + 1] - h.t_row_ptr[r]);
@@ -1416,6 +1627,12 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 d.D = cfg->training ? (float *)(base + q.D) : nullptr;
                 d.G[0] = gw ? (float *)(base + q.G[0]) : nullptr;
                 d.G[1] = gw ? (float *)(base + q.G[1]) : nullptr;
+                d.lm = want_lm ? (int2 *)(base + q.lm) : nullptr;
+                d.lm_off = want_lm ? (const int32_t *)(base + q.lm_off) : nullptr;
+                d.lm_row = want_lm ? (const int32_t *)(base + q.lm_row) : nullptr;
+                d.lm_bias = want_lm ? (float *)(base + q.lm_bias) : nullptr;
+                d.n_blocks = want_lm ? (int32_t)q.lm_blocks : 0;
+                d.pad2_ = 0;
                 d.X_prev = !cfg->training ? nullptr
                            : l == 0       ? (float *)(base + pl.x0)
                                           : net->layers[l - 1].X;
@@ -1433,6 +1650,14 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 UP(d.t_perm, h.t_perm.data(), 4 * nnz);
                 UP(d.sched, h.sched.data(), 16 * (size_t)y.n_out);
                 UP(d.t_sched, h.t_sched.data(), 16 * (size_t)y.n_in);
+                if (want_lm) {
+                    if (h.lm.size() != q.lm_entries)
+                        return fail_free(fail(nullptr, SDNN_EINVAL, "layer %d: lane-major copy does not match its plan", l + 1));
+                    UP(d.lm, h.lm.data(), 8 * h.lm.size());
+                    UP(d.lm_off, h.lm_off.data(), 4 * h.lm_off.size());
+                    UP(d.lm_row, h.lm_row.data(), 4 * h.lm_row.size());
+                    UP(d.lm_bias, h.lm_bias.data(), 4 * h.lm_bias.size());
+                }
             }
             SYNC(); // the group's host arrays are reused by the next group
         }
@@ -1469,6 +1694,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
             net->d_n_live[k] = (int32_t *)(base + pl.n_live[k]);
         }
     }
+    net->lds_ready = want_lm;
     net->bias_nonpos = true;
     for (int32_t l = 1; l < n_layers; ++l)
         if (layers[l].bias)
@@ -1675,6 +1901,26 @@ static int launch_spmm(sdnn_net *net, const LayerDev &d, const float *in, float 
     return SDNN_OK;
 }
 
+// Whether the single-launch LDS-resident forward is the faster way to run this block of B samples.
+static bool lds_forward_pays(const sdnn_net *net, int B)
+{
+    if (!net->lds_ready || net->cfg.lds_forward == SDNN_LDS_OFF) return false;
+    for (const LayerDev &d : net->layers)
+        if (d.n_out == 0) return false; // an empty layer: leave it to the general path
+    if (net->cfg.lds_forward == SDNN_LDS_ON) return true;
+    // Measured on nets of 32-entry rows (N = 1024 and 4096, 120 layers): the single launch takes about
+    // 2 us + 0.13 ns per stored entry per layer for every round of workgroups (one workgroup of LDS_T samples
+    // per CU), the per-layer kernels about 4.5 us + 0.21 ps per entry and sample per layer.
+    int64_t nnz = 0;
+    for (const LayerDev &d : net->layers) nnz += d.nnz;
+    const double nnz_layer = (double)nnz / (double)net->n_layers;
+    const int wgs = (B + LDS_T - 1) / LDS_T;
+    const int rounds = (wgs + net->n_cu - 1) / std::max(net->n_cu, 1);
+    const double t_fused = rounds * (2.0e-6 + 0.13e-9 * nnz_layer);
+    const double t_layers = 4.5e-6 + 0.21e-12 * nnz_layer * (double)B;
+    return t_fused < t_layers;
+}
+
 // Eq. 3 for l = 1..L.  Inference nets stage the activations between the layers in ping / pong
 // (each at least 4 * max_n * B bytes); training nets keep every X_l in the workspace and ignore them.
 static int forward_impl(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL, void *stream_, float *ping,
@@ -1684,6 +1930,26 @@ static int forward_impl(sdnn_net *net, const float *d_X0, int32_t B, float *d_XL
     hipStream_t stream = (hipStream_t)stream_;
     net->state = ST_IDLE;
     const int L = net->n_layers;
+    if (lds_forward_pays(net, B)) {
+        const void *fn = net->cfg.activation == ACT_SIGMOID ? (const void *)k_fwd_lds<ACT_SIGMOID> : (const void *)k_fwd_lds<ACT_RELU_CAP>;
+        int buf_floats = LDS_T * ((net->max_n + 3) & ~3);
+        const size_t lds_bytes = 2 * sizeof(float) * (size_t)buf_floats;
+        if (!net->lds_attr_set) { // more than the default 64 KiB of dynamic LDS per workgroup
+            HIP_TRY(net, hipFuncSetAttribute((const void *)k_fwd_lds<ACT_SIGMOID>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 4 * LDS_T * LDS_MAX_N));
+            HIP_TRY(net, hipFuncSetAttribute((const void *)k_fwd_lds<ACT_RELU_CAP>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 4 * LDS_T * LDS_MAX_N));
+            net->lds_attr_set = true;
+        }
+        const LayerDev *layers = net->d_layers;
+        int n_layers = L, b = B, vec_io = (B % 4 == 0 && aligned(d_X0, 16) && aligned(d_XL, 16)) ? 1 : 0;
+        float cap = net->cfg.act_cap;
+        void *args[] = {(void *)&layers, (void *)&n_layers, (void *)&d_X0, (void *)&d_XL, (void *)&b, (void *)&buf_floats,
+                        (void *)&cap, (void *)&vec_io};
+        HIP_TRY(net, hipLaunchKernel(fn, dim3((unsigned)((B + LDS_T - 1) / LDS_T)), dim3(64 * LDS_WAVES), args, lds_bytes, stream));
+        HIP_TRY(net, hipGetLastError());
+        net->B = B;
+        net->state = ST_FORWARD;
+        return SDNN_OK;
+    }
     const float *in = d_X0;
     if (training) {
         const size_t bytes = 4 * (size_t)net->layers[0].n_in * B;
@@ -2073,6 +2339,10 @@ extern "C" int sdnn_set_weights(sdnn_net *net, int32_t layer, const float *d_val
     if (!rc && d_bias) {
         rc = copy_dd(net, d.bias, d_bias, 4 * (size_t)d.n_out, stream_);
         if (layer > 1) net->bias_nonpos = false; // device data: its signs are not inspected
+    }
+    if (!rc && (d_values || d_bias) && d.lm && d.n_blocks > 0) { // keep the lane-major copy current
+        hipLaunchKernelGGL(k_lm_refresh, dim3((unsigned)d.n_blocks), dim3(64), 0, (hipStream_t)stream_, net->d_layers + (layer - 1));
+        HIP_TRY(net, hipGetLastError());
     }
     return rc;
 }

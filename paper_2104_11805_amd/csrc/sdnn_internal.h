@@ -26,4 +26,13 @@ struct LayerDev {
     float *X;                 // X_l      [n_out][B]  (training mode)
     float *D;                 // Delta_l  [n_out][B]  (training mode)
     float *G[2];              // [nnz] each: gradient of the stored entries over one half of the batch (training mode)
+    // lane-major copy of W for the LDS-resident forward (small inference nets; NULL otherwise): the rows,
+    // longest first, in blocks of 64; block b holds, for k = 0 .. K_b - 1, entry k of its 64 rows side by
+    // side (lm[lm_off[b] + 64 k + lane] = {column, weight bits}), padded with {0, 0.0f} up to the block's
+    // longest row, so that lane r of a wavefront walks row r with coalesced loads
+    int2 *lm;                 // [lm_off[n_blocks]]
+    const int32_t *lm_off;    // [n_blocks + 1], multiples of 64
+    const int32_t *lm_row;    // [64 n_blocks]: the row of each lane, -1 past the last row
+    float *lm_bias;           // [64 n_blocks]: the bias of that row
+    int32_t n_blocks, pad2_;
 };

@@ -21,6 +21,7 @@ SDNN_ACT_RELU_CAP, SDNN_ACT_SIGMOID = 0, 1
 SDNN_FUSE_AUTO, SDNN_FUSE_ON, SDNN_FUSE_OFF = 0, 1, -1
 SDNN_NOALLOC_SCRATCH_BYTES = 16 << 20
 SDNN_PANEL_AUTO, SDNN_PANEL_OFF = 0, -1
+SDNN_LDS_AUTO, SDNN_LDS_ON, SDNN_LDS_OFF = 0, 1, -1
 
 
 class SdnnError(RuntimeError):
@@ -37,7 +38,7 @@ class sdnn_layer(C.Structure):
 class sdnn_config(C.Structure):
     _fields_ = [("act_cap", C.c_float), ("max_batch", C.c_int32), ("training", C.c_int32),
                 ("update_bias", C.c_int32), ("activation", C.c_int32), ("fuse_gradient", C.c_int32),
-                ("panel_cols", C.c_int32), ("reorder_rows", C.c_int32)]
+                ("panel_cols", C.c_int32), ("reorder_rows", C.c_int32), ("lds_forward", C.c_int32)]
 
 
 # name -> (restype, argtypes); every symbol include/sdnn.h declares
@@ -168,7 +169,7 @@ class Net:
 
     def __init__(self, layers: Sequence, act_cap: float, max_batch: int, training: bool = True,
                  update_bias: bool = True, device: str = "cuda:0", activation: str = "relu",
-                 fuse_gradient: int = 0, panel_cols: int = 0, reorder_rows: bool = False):
+                 fuse_gradient: int = 0, panel_cols: int = 0, reorder_rows: bool = False, lds_forward: int = 0):
         import torch
         self._handle = None
         self._keep = []
@@ -182,7 +183,7 @@ class Net:
                                 None if bi is None else _hp(bi).value)
         self.cfg = sdnn_config(float(act_cap), int(max_batch), int(training), int(update_bias),
                                {"relu": SDNN_ACT_RELU_CAP, "sigmoid": SDNN_ACT_SIGMOID}[activation],
-                               int(fuse_gradient), int(panel_cols), int(reorder_rows))
+                               int(fuse_gradient), int(panel_cols), int(reorder_rows), int(lds_forward))
         nbytes = C.c_size_t(0)
         _check(lib().sdnn_workspace_bytes(arr, len(layers), C.byref(self.cfg), C.byref(nbytes)))
         self.device = torch.device(device)

@@ -30,6 +30,16 @@ int main()
         if (sdnn_row_schedule(n_out, row_ptr.data(), order.data())) return 6;
         for (int r = 1; r < n_out; ++r)
             if (row_ptr[order[r] + 1] - row_ptr[order[r]] > row_ptr[order[r - 1] + 1] - row_ptr[order[r - 1]]) return 7;
+        // clustering by shared columns and dealing to the XCDs: both give permutations of the rows
+        {
+            std::vector<int32_t> corder(n_out), cluster_of(n_out), dealt(n_out), seen(n_out, 0);
+            if (sdnn_cluster_rows(n_out, n_in, row_ptr.data(), col.data(), 1 + (int)(rnd() % 9), corder.data(), cluster_of.data())) return 10;
+            if (sdnn_deal_rows_to_xcds(n_out, row_ptr.data(), corder.data(), dealt.data())) return 11;
+            for (int r = 0; r < n_out; ++r) {
+                if (dealt[r] < 0 || dealt[r] >= n_out || seen[dealt[r]]++) return 12;
+                if (cluster_of[r] < 0 || cluster_of[r] >= n_out) return 13;
+            }
+        }
         // malformed inputs must be rejected, not read out of bounds
         if (nnz > 0) {
             std::vector<int32_t> bad(col);

@@ -98,3 +98,60 @@ def test_panel_sweep_by_policy_on_a_wide_layer_and_long_rows_fall_back():
     g = P.gpu_train_step(work, work.x_train, fuse_gradient=-1, panel_cols=32)
     o = P.oracle_train_step(work, work.x_train)
     P.compare_step(g, o, "panel refused for long rows")
+
+
+@pytest.mark.parametrize("activation", ["relu", "sigmoid"])
+@pytest.mark.parametrize("b", [1, 3, 64, 130])
+def test_lds_resident_forward_small_ragged_nets(b, activation):
+    """The single-launch forward with activations in LDS: rectangular layers, ragged rows (some empty, some longer
+    than a block's neighbours), a partial last group of samples; same bits as the per-layer kernels and the oracle."""
+    sizes = (150, 333, 97, 210, 64)
+    layers = [wl.random_layer(1200 + l, sizes[l + 1], sizes[l], 0.15, scale=0.5) for l in range(4)]
+    layers[1] = wl.ragged_layer(1250, sizes[2], sizes[1], 0.05, 3, 200, 3, 60)
+    x = wl.normal_inputs(1290, sizes[0], b)
+    cap = float("inf") if activation == "sigmoid" else 1.3
+    ref = P.ORACLES[activation].forward(layers, x, cap)[-1]
+    outs = {}
+    for mode in (sdnn.SDNN_LDS_ON, sdnn.SDNN_LDS_OFF):
+        net = sdnn.Net(layers, cap, max(b, 4), training=False, activation=activation, lds_forward=mode)
+        out = torch.full((sizes[-1], b), -3.0, device=P.DEV)
+        net.sdnn_forward(P.dev(x), out)
+        outs[mode] = P.host(out)
+        net.close()
+    P.assert_forward_close(outs[sdnn.SDNN_LDS_ON], ref, "lds forward")
+    if activation == "relu":
+        assert np.array_equal(outs[sdnn.SDNN_LDS_ON], ref)
+    assert np.array_equal(outs[sdnn.SDNN_LDS_ON], outs[sdnn.SDNN_LDS_OFF])
+
+
+def test_lds_resident_forward_benchmark_nets_and_replaced_weights():
+    work = wl.make_config(2, n_layers=10, density=0.37, b_infer=260, b_train=64)
+    ref = P.O32.forward(work.layers, work.x_infer, work.act_cap)
+    assert 0.05 < (ref[-1] > 0).mean() and (ref[-1] < 32).any()
+    net = sdnn.Net(work.layers, work.act_cap, 260, training=False, lds_forward=sdnn.SDNN_LDS_ON)
+    out = torch.empty(4096, 260, device=P.DEV)
+    net.sdnn_forward(P.dev(work.x_infer), out)
+    assert np.array_equal(P.host(out), ref[-1])
+    # new weights for two layers: the lane-major copy must follow
+    rng = np.random.default_rng(5)
+    for k in (1, 7):
+        lay = work.layers[k - 1]
+        lay.values = (lay.values * rng.uniform(0.5, 1.5, lay.nnz)).astype(np.float32)
+        lay.bias = (lay.bias * 0.5).astype(np.float32)
+        net.sdnn_set_weights(k, P.dev(lay.values), P.dev(lay.bias))
+    ref2 = P.O32.forward(work.layers, work.x_infer, work.act_cap)[-1]
+    assert not np.array_equal(ref2, ref[-1])
+    net.sdnn_forward(P.dev(work.x_infer), out)
+    assert np.array_equal(P.host(out), ref2)
+    out2 = torch.empty(4096, 260, device=P.DEV)
+    net.sdnn_forward_noalloc(P.dev(work.x_infer), out2)
+    assert torch.equal(out, out2)
+    net.close()
+    # a net wider than LDS holds keeps the per-layer kernels, whatever the option says
+    wide = [wl.regular_layer(77, 4100, 8, 0.125, -0.1)]
+    net = sdnn.Net(wide, 32.0, 8, training=False, lds_forward=sdnn.SDNN_LDS_ON)
+    x = wl.binary_inputs(78, 4100, 8, 0.5)
+    out = torch.empty(4100, 8, device=P.DEV)
+    net.sdnn_forward(P.dev(x), out)
+    assert np.array_equal(P.host(out), P.O32.forward(wide, x, 32.0)[-1])
+    net.close()

@@ -108,9 +108,22 @@ def test_workspace_bytes_and_argument_errors_without_gpu():
     nnz = sum(x.nnz for x in net.layers)
     # CSR + transposed index (5 x 4 bytes per entry) + activations and deltas
     assert train_bytes >= 20 * nnz + 4 * 16 * (2 * (9 + 6 + 8) + 7)
-    cfg_inf = sdnn.sdnn_config(float("inf"), 16, 0, 1, 0)
+    cfg_inf = sdnn.sdnn_config(float("inf"), 16, 0, 1, 0, 0, 0, 0, sdnn.SDNN_LDS_OFF)
     assert l.sdnn_workspace_bytes(arr, 3, C.byref(cfg_inf), C.byref(n)) == 0
     assert 0 < n.value < train_bytes
+    # an inference net of narrow layers also holds the lane-major copy for the LDS-resident forward:
+    # 8 bytes per entry of the 64-row blocks, each as deep as its longest row
+    plain_inf = n.value
+    cfg_lds = sdnn.sdnn_config(float("inf"), 16, 0, 1, 0)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(cfg_lds), C.byref(n)) == 0
+    padded = sum(64 * int(np.diff(x.row_ptr).max()) for x in net.layers)       # one block per layer here
+    assert n.value >= plain_inf + 8 * padded
+    bad = sdnn.sdnn_config(32.0, 4, 0, 1, 0, 0, 0, 0, 5)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
+    bad = sdnn.sdnn_config(32.0, 4, 0, 1, 0, 0, -2)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
+    bad = sdnn.sdnn_config(32.0, 4, 0, 1, 0, 0, 0, 2)
+    assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
     # argument errors are reported before any GPU work
     bad = sdnn.sdnn_config(float("inf"), 0, 1, 1, 0)
     assert l.sdnn_workspace_bytes(arr, 3, C.byref(bad), C.byref(n)) == sdnn.SDNN_EINVAL
@@ -160,7 +173,7 @@ def test_malformed_layer_is_rejected_by_create_without_gpu():
 
 
 def test_host_setup_routines_under_sanitizers(tmp_path):
-    """sdnn_setup.cpp (CSR check, transposed index, row schedule) with ASan + UBSan on the host."""
+    """sdnn_setup.cpp (CSR check, transposed index, row schedule, row clustering and dealing) with ASan + UBSan on the host."""
     import shutil
     import subprocess
     if shutil.which("g++") is None:
@@ -169,7 +182,7 @@ def test_host_setup_routines_under_sanitizers(tmp_path):
     # the HIP vector-type header is only needed for device descriptors: give the host build a stand-in
     stub = tmp_path / "hip"
     stub.mkdir()
-    (stub / "hip_vector_types.h").write_text("struct int4 { int x, y, z, w; };\n")
+    (stub / "hip_vector_types.h").write_text("struct int4 { int x, y, z, w; };\nstruct int2 { int x, y; };\n")
     cmd = ["g++", "-std=c++17", "-g", "-O1", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
            "-I", str(tmp_path), os.path.join(ROOT, "tests", "host_setup_sanitize.cpp"),
            os.path.join(ROOT, "paper_2104_11805_amd", "csrc", "sdnn_setup.cpp"), "-o", str(exe)]
