@@ -79,7 +79,8 @@ def run_config(cfg, args, steps, warmup, headline):
 
     # ---- training step --------------------------------------------------
     t0 = time.time()
-    net = sdnn.Net(work.layers, work.act_cap, Bt, training=True)
+    opts = dict(panel_cols=args.panel_cols) if headline else {}
+    net = sdnn.Net(work.layers, work.act_cap, Bt, training=True, **opts)
     torch.cuda.synchronize()
     create_s = time.time() - t0
     log(f"config {cfg}: training net created in {create_s:.1f} s, workspace {net.workspace_bytes / 2**30:.2f} GiB")
@@ -211,7 +212,8 @@ def run_config(cfg, args, steps, warmup, headline):
     if not args.no_inference:
         block = (args.infer_block if headline else 0) or min(Bi, 1024 if N >= 65536 else Bi)
         t0 = time.time()
-        inet = sdnn.Net(work.layers, work.act_cap, block, training=False)
+        iopts = dict(panel_cols=args.panel_cols, lds_forward=args.lds_forward) if headline else {}
+        inet = sdnn.Net(work.layers, work.act_cap, block, training=False, **iopts)
         torch.cuda.synchronize()
         icreate_s = time.time() - t0
         blocks = [(s, min(block, Bi - s)) for s in range(0, Bi, block)]
@@ -281,7 +283,7 @@ def run_config(cfg, args, steps, warmup, headline):
                "sample": f"one training step on the first {Ls} of {L} layers, full minibatch {Bt} ({cs:.1f} s)"}
         # the same oracle on one thread, on a shorter depth prefix
         n_all = orc.threads()
-        L1 = int(max(1, min(Ls, (args.cpu_edge_visits / 20) // per_layer)))
+        L1 = int(max(1, min(Ls, (args.cpu_edge_visits / 6) // per_layer)))
         orc.set_threads(1)
         t0 = time.perf_counter()
         orc.train_step(work.layers[:L1], work.x_train, work.act_cap, dfn, work.lr)
@@ -327,12 +329,16 @@ def main():
     ap.add_argument("--others", type=str, default=None,
                     help="comma-separated configurations for the key other_configs (default: the other four when "
                          "the headline runs at full depth with nominal inputs; 'none' for none)")
+    ap.add_argument("--gather-ceiling", action="store_true",
+                    help="what a pure stream of random row gathers reaches, by table size and row width (the ceiling "
+                         "of the product kernels' operand gathers)")
     ap.add_argument("--reorder-study", action="store_true",
                     help="row order chosen for gather locality (reorder_rows) on and off: a structured topology "
                          "(rows in groups of 32 share their columns) and the random config-2 pattern")
     ap.add_argument("--reorder", choices=["both", "0", "1"], default="both",
                     help="--reorder-study: which settings of reorder_rows to run (one at a time for counter runs)")
-    ap.add_argument("--panel-cols", type=int, default=0, help="sdnn_config.panel_cols for --reorder-study (0 auto, -1 off)")
+    ap.add_argument("--panel-cols", type=int, default=0, help="sdnn_config.panel_cols of the headline nets and of --reorder-study (0 auto, -1 off)")
+    ap.add_argument("--lds-forward", type=int, default=0, help="sdnn_config.lds_forward of the headline inference net (0 auto, 1 on, -1 off)")
     ap.add_argument("--time-budget", type=float, default=400.0,
                     help="seconds since program start after which no further other_configs entry is begun")
     args = ap.parse_args()
@@ -351,6 +357,8 @@ def main():
         return paper_setup_bench(args, np, torch, sdnn, wl)
     if args.reorder_study:
         return reorder_study(args, np, torch, sdnn, wl)
+    if args.gather_ceiling:
+        return gather_ceiling(args, np, torch, sdnn)
 
     head = run_config(args.config, args, args.steps, args.warmup, headline=True)
     if args.others is None:
@@ -443,6 +451,40 @@ def paper_setup_bench(args, np, torch, sdnn, wl):
                                                       "note": "paper Fig. 4, other hardware and the real nets: context only"},
         "cpu_baseline": cpu}))
     net.close()
+
+
+def gather_ceiling(args, np, torch, sdnn):
+    """Random gathers of rows of 64*v floats from tables of 1 MiB .. 256 MiB, 8 / 16 / 32 wavefronts per CU, each
+    streaming 256 gathers with 8 in flight (sdnn_gather_probe): TB/s and rows per microsecond."""
+    dev = "cuda:0"
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    per_wave, reps, rows_out = 256, 10, []
+    for v in (1, 4):
+        for mib in (1, 4, 16, 64, 256):
+            n_rows = mib * 2 ** 20 // (256 * v)
+            table = torch.zeros(n_rows, 64 * v, device=dev)
+            for wpc in (8, 16, 32):
+                n_waves = n_cu * wpc
+                idx = torch.randint(0, n_rows, (n_waves * per_wave,), device=dev, dtype=torch.int32,
+                                    generator=torch.Generator(device=dev).manual_seed(7))
+                out = torch.empty(n_waves * 64, device=dev)
+                for _ in range(3):
+                    sdnn.sdnn_gather_probe(table, v, idx, n_waves, per_wave, out)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    sdnn.sdnn_gather_probe(table, v, idx, n_waves, per_wave, out)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                r = {"row_bytes": 256 * v, "table_MiB": mib, "waves_per_cu": wpc, "us": round(us, 2),
+                     "TB_per_s": round(n_waves * per_wave * 256.0 * v / us * 1e-6, 2),
+                     "rows_per_us": round(n_waves * per_wave / us, 1)}
+                rows_out.append(r)
+                log(str(r))
+            del table
+    print(json.dumps({"study": "ceiling of random row gathers (sdnn_gather_probe)", "gathers_per_wavefront": per_wave,
+                      "in_flight_per_wavefront": 8, "results": rows_out}))
 
 
 def reorder_study(args, np, torch, sdnn, wl):

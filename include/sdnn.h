@@ -140,7 +140,8 @@ int sdnn_workspace_bytes(const sdnn_layer *layers, int32_t n_layers, const sdnn_
 
 /* Validates the layers (consecutive layers must agree: n_in(l+1) == n_out(l)),
  * builds the transposed index of every W_l and the row schedules, and copies
- * everything into d_workspace (device, 256-byte aligned, >= workspace bytes).
+ * everything into d_workspace (device, >= workspace bytes; 256-byte aligned at least, a 2 MiB
+ * boundary for full speed: the large arrays are placed on multiples of up to 2 MiB from its start).
  * Synchronises `stream` before returning.  On failure *out is NULL. */
 int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg,
                 void *d_workspace, size_t workspace_bytes, void *stream, sdnn_net **out);
@@ -215,6 +216,16 @@ int sdnn_mse_dloss(const float *d_XL, const float *d_Y, int32_t n, int32_t B, fl
  *  =>  d_out = (softmax - onehot)/B on those rows, 0 elsewhere.  d_labels int32[B]. */
 int sdnn_softmax_ce_dloss(const float *d_XL, const int32_t *d_labels, int32_t n, int32_t B,
                           int32_t n_classes, float *d_out, void *stream);
+
+/* ---- measurement aid ---------------------------------------------------------
+ * The ceiling of the gather path that the products of Eqs. 3 and 7 depend on: n_waves wavefronts
+ * (a multiple of 4) each stream per_wave (a multiple of 8) gathers of rows of 64*v floats (v = 1, 2, 4:
+ * one v-float piece per lane) from d_table [table_rows][64*v], the rows given by d_idx
+ * [n_waves * per_wave] (each in [0, table_rows): out-of-range rows read as zeros), 8 gathers in flight
+ * per wavefront, no arithmetic beyond a running sum stored to d_out [n_waves * 64].  Timed by the caller;
+ * bench.py --gather-ceiling tabulates it by table size. */
+int sdnn_gather_probe(const float *d_table, int32_t table_rows, int32_t v, const int32_t *d_idx, int32_t n_waves,
+                      int32_t per_wave, float *d_out, void *stream);
 
 /* ---- host-only pieces of the setup, exported so they can be checked
  *      without a GPU (all pointers HOST) ------------------------------------ */

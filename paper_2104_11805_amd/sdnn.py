@@ -60,6 +60,7 @@ SIGNATURES = {
     "sdnn_layer_shape": (C.c_int, [_P, _I32, C.POINTER(_I32), C.POINTER(_I32), _I64P]),
     "sdnn_mse_dloss": (C.c_int, [_P, _P, _I32, _I32, _P, _P]),
     "sdnn_softmax_ce_dloss": (C.c_int, [_P, _P, _I32, _I32, _I32, _P, _P]),
+    "sdnn_gather_probe": (C.c_int, [_P, _I32, _I32, _P, _I32, _I32, _P, _P]),
     "sdnn_check_csr": (C.c_int, [_I32, _I32, _P, _P]),
     "sdnn_transpose_pattern": (C.c_int, [_I32, _I32, _P, _P, _P, _P, _P]),
     "sdnn_row_schedule": (C.c_int, [_I32, _P, _P]),
@@ -188,12 +189,15 @@ class Net:
         _check(lib().sdnn_workspace_bytes(arr, len(layers), C.byref(self.cfg), C.byref(nbytes)))
         self.device = torch.device(device)
         self.workspace_bytes = nbytes.value
-        # torch's caching allocator returns 512-byte aligned blocks
-        self.workspace = torch.empty(max(nbytes.value, 256), dtype=torch.uint8, device=self.device)
+        # the library lays its large arrays out on multiples of up to 2 MiB relative to the workspace: hand it a
+        # workspace that starts on a 2 MiB boundary itself (torch only promises 512 bytes)
+        big = 2 << 20
+        self.workspace = torch.empty(max(nbytes.value, 256) + big, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + big - 1) // big * big
         h = C.c_void_p()
         with torch.cuda.device(self.device):
             _check(lib().sdnn_create(arr, len(layers), C.byref(self.cfg),
-                                     C.c_void_p(self.workspace.data_ptr()), nbytes.value,
+                                     C.c_void_p(base), nbytes.value,
                                      _stream_ptr(), C.byref(h)))
         self._handle = h
         self._keep = []
@@ -281,3 +285,9 @@ def sdnn_softmax_ce_dloss(xl, labels_i32, n_classes: int, out=None, stream=None)
     _check(lib().sdnn_softmax_ce_dloss(_dp(xl), _dp(labels_i32), xl.shape[0], xl.shape[1], n_classes,
                                        _dp(out), _stream_ptr(stream)))
     return out
+
+
+def sdnn_gather_probe(table, v: int, idx_i32, n_waves: int, per_wave: int, out, stream=None):
+    """table [rows][64*v] fp32, idx int32 [n_waves*per_wave], out fp32 [n_waves*64]: all device tensors."""
+    _check(lib().sdnn_gather_probe(_dp(table), table.shape[0], int(v), _dp(idx_i32), int(n_waves), int(per_wave), _dp(out),
+                                   _stream_ptr(stream)))
