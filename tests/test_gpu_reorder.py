@@ -64,7 +64,8 @@ def test_reordered_rows_inference_and_skip_dead():
     net.close()
 
 
-@pytest.mark.parametrize("b,cols,n", [(37, 7, 333), (64, 50, 333), (100, 1000, 333), (130, 16, 333), (520, 100, 5000)])
+@pytest.mark.parametrize("b,cols,n", [(37, 7, 333), (64, 50, 333), (100, 1000, 333), (130, 16, 333), (128, 9, 333),
+                                      (64, 300, 5000), (520, 100, 5000)])
 def test_panel_sweep_forced_on_small_nets(b, cols, n):
     """panel_cols forced: many narrow panels, ragged rows (some empty), partial last tile; the last case has
     eight or more tiles, so every XCD sweeps its own tiles with several rows per wavefront."""
@@ -76,6 +77,9 @@ def test_panel_sweep_forced_on_small_nets(b, cols, n):
     g = P.gpu_train_step(work, work.x_train, fuse_gradient=-1, panel_cols=cols)
     o = P.oracle_train_step(work, work.x_train)
     assert P.compare_step(g, o, f"panel b={b} cols={cols}")["live_g"] == 3
+    if b <= 64 or b == 128:      # the fused backward sweep next to a panel-swept forward
+        g = P.gpu_train_step(work, work.x_train, fuse_gradient=1, panel_cols=cols)
+        assert P.compare_step(g, o, f"fused panel b={b} cols={cols}")["live_g"] == 3
     net = sdnn.Net(layers, 1.2, b, training=False, panel_cols=cols)
     out = torch.empty(sizes[-1], b, device=P.DEV)
     net.sdnn_forward(P.dev(work.x_train), out)
@@ -87,7 +91,8 @@ def test_panel_sweep_by_policy_on_a_wide_layer_and_long_rows_fall_back():
     """65536 columns: the policy sweeps in panels (forward and the separate backward product; rows per
     wavefront chosen from the row count); a layer with a row of more than 64 entries does not."""
     work = wl.make_config(4, n_layers=3, density=0.60, b_infer=64, b_train=64)
-    for opts in (dict(fuse_gradient=-1), dict(fuse_gradient=-1, panel_cols=-1), dict(fuse_gradient=-1, reorder_rows=True)):
+    for opts in (dict(fuse_gradient=-1), dict(fuse_gradient=-1, panel_cols=-1), dict(fuse_gradient=-1, reorder_rows=True),
+                 dict(fuse_gradient=1), dict(fuse_gradient=1, panel_cols=-1)):
         g = P.gpu_train_step(work, work.x_train, **opts)
         if "o" not in locals():
             o = P.oracle_train_step(work, work.x_train)
