@@ -914,7 +914,9 @@ k_update_b1(const LayerDev *__restrict__ layers, int layer0, int lpr_log2, float
 //   emit == 0: vals -= lr*g, bias -= lr*gb (if update_bias)
 //   emit == 1: g_out / gb_out receive the gradient of the single layer
 // ---------------------------------------------------------------------------
-template <int V>
+// HOLD > 0: the batch has at most 16 * V * HOLD samples and the lane keeps its share of the row of Delta in
+// registers for the whole row (long rows: otherwise it is read again for every 32-entry chunk).
+template <int V, int HOLD>
 __global__ void __launch_bounds__(64 * UPD_WAVES)
 k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int interleave, int rows_per_wave, int B,
          float lr, int update_bias, int emit, float *__restrict__ g_out, float *__restrict__ gb_out)
@@ -957,6 +959,16 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
     if (emit && g_out == nullptr) continue;
 
     const int sg = lane & 15, eg = lane >> 4;
+    float dh[HOLD > 0 ? HOLD : 1][V];
+    if constexpr (HOLD > 0) {
+#pragma unroll
+        for (int t = 0; t < HOLD; ++t) {
+            const int s = sg * V + 16 * V * t;
+#pragma unroll
+            for (int v = 0; v < V; ++v) dh[t][v] = 0.0f;
+            if (s < B) ldv<V>(drow + s, dh[t]);
+        }
+    }
     for (int base = beg; base < end; base += 32) {
         const int p0 = base + eg * 8;
         size_t coff[8];
@@ -973,9 +985,7 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
         double a[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = 0.0;
-        for (int s = sg * V; s < B; s += 16 * V) {
-            float df[V];
-            ldv<V>(drow + s, df);
+        auto pass = [&](int s, const float (&df)[V]) { // the chunk's 8 entries against V samples of this lane
             float x[8][V];
 #pragma unroll
             for (int k = 0; k < 8; ++k) ldv<V>(xp + coff[k] + s, x[k]);
@@ -986,6 +996,19 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
             for (int k = 0; k < 8; ++k)
 #pragma unroll
                 for (int v = 0; v < V; ++v) a[k] = fma(d[v], (double)x[k][v], a[k]);
+        };
+        if constexpr (HOLD > 0) {
+#pragma unroll
+            for (int t = 0; t < HOLD; ++t) {
+                const int s = sg * V + 16 * V * t;
+                if (s < B) pass(s, dh[t]);
+            }
+        } else {
+            for (int s = sg * V; s < B; s += 16 * V) {
+                float df[V];
+                ldv<V>(drow + s, df);
+                pass(s, df);
+            }
         }
         // 16-lane transpose-reduce: 8 values/lane -> 1 value/lane (register indices are compile-time)
         {
@@ -2283,11 +2306,14 @@ static int launch_update(sdnn_net *net, int layer0, int n_layers, float lr, int 
     for (int l0 = 0; l0 < n_layers; l0 += 65535) {
         const int nl = std::min(65535, n_layers - l0);
         dim3 grid(interleave ? 8u * n_rg : n_rg, (unsigned)(interleave ? (nl + 7) / 8 : nl));
-        if (V == 4)
-            hipLaunchKernelGGL(k_update<4>, grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
+        if (V == 4 && rpw == 1 && B <= 256) // long rows: the row of Delta stays in registers
+            hipLaunchKernelGGL((k_update<4, 4>), grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
+                               layer0 + l0, nl, interleave, rpw, B, lr, net->cfg.update_bias, emit, g, gb);
+        else if (V == 4)
+            hipLaunchKernelGGL((k_update<4, 0>), grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
                                layer0 + l0, nl, interleave, rpw, B, lr, net->cfg.update_bias, emit, g, gb);
         else
-            hipLaunchKernelGGL(k_update<1>, grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
+            hipLaunchKernelGGL((k_update<1, 0>), grid, dim3(64 * UPD_WAVES), 0, stream, net->d_layers,
                                layer0 + l0, nl, interleave, rpw, B, lr, net->cfg.update_bias, emit, g, gb);
         HIP_TRY(net, hipGetLastError());
     }
