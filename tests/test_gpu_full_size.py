@@ -116,3 +116,14 @@ def test_config5_full_size_training_step(cfg5):
 def test_config5_full_size_inference(cfg5):
     got, ref = _inference(cfg5, cfg5.x_infer, 2048, _sample_cols(2048, 5), "cfg5 inference")
     assert 0.3 < (ref > 0).mean() < 0.7
+
+
+def test_config4_full_size_sigmoid_training_step_is_live_in_every_layer(cfg4):
+    """Config 4's nets and minibatch with the sigmoid of the paper's own training setup (Section 6.1): no neuron
+    dies or saturates, so every layer of the full-size workspace carries non-zero activations, deltas (down to
+    the subnormal range in the first layers: the delta shrinks by about 0.4 per layer going back) and gradients."""
+    work = wl.Workload("cfg4-sigmoid", cfg4.layers, float("inf"), cfg4.x_infer[:, :64], 64, "mse", 0.01,
+                       targets=cfg4.targets, activation="sigmoid")
+    st = P.full_step_compare(work, work.x_train, "cfg4 sigmoid", log=_log)
+    assert st["live_x"] == 120 and st["live_d"] >= 100 and st["live_g"] >= 100
+    assert st["bitexact_d"] >= 100

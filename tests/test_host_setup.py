@@ -159,6 +159,13 @@ def test_workspace_bytes_and_argument_errors_without_gpu():
     assert l.sdnn_backward(None, None, None) == sdnn.SDNN_EINVAL
     assert l.sdnn_sgd_step(None, 0.1, None) == sdnn.SDNN_EINVAL
     l.sdnn_destroy(None)
+    # the measurement aid checks its arguments before it touches the GPU
+    assert l.sdnn_gather_probe(None, 16, 1, None, 4, 8, None, None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_gather_probe(C.c_void_p(4096), 16, 3, C.c_void_p(4096), 4, 8, C.c_void_p(4096), None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_gather_probe(C.c_void_p(4096), 16, 1, C.c_void_p(4096), 6, 8, C.c_void_p(4096), None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_gather_probe(C.c_void_p(4096), 16, 1, C.c_void_p(4096), 4, 12, C.c_void_p(4096), None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_gather_probe(C.c_void_p(4096), 1 << 24, 4, C.c_void_p(4096), 4, 8, C.c_void_p(4096), None) == sdnn.SDNN_EINVAL
+    assert l.sdnn_forward_noalloc(None, None, 1, None, None) == sdnn.SDNN_EINVAL
 
 
 def test_malformed_layer_is_rejected_by_create_without_gpu():
