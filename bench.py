@@ -40,15 +40,17 @@ def layer_bytes(n, nnz, b, fused):
     """Algorithmic HBM bytes per layer of each pass (every array moved once; gathers served on chip).
 
     forward   index + values (8 nnz), row schedule (16 n), bias (4 n), X in and X out
-    backward  transposed index + position (8 nnz), values through it (4 nnz), schedule, Delta in, X mask, Delta out;
-              the fused sweep also writes the gradient of the stored entries (4 nnz)
+    backward  separate: transposed index + position (8 nnz), values through it (4 nnz), schedule, Delta in, X mask,
+              Delta out; fused sweep: transposed index + values in that order (8 nnz), gradient written (4 nnz), the rest
+              the same
     update    separate: index (4 nnz), values read + written (8 nnz), schedule, bias r/w, Delta, X
-              after a fused sweep: values r/w + gradient read (12 nnz), bias r/w, Delta (bias gradient)
+              after a fused sweep: transposed-order values r/w + gradient read (12 nnz), then the CSR copy rebuilt
+              (inverse position, value read, value written: 12 nnz), bias r/w, Delta (bias gradient)
     """
     act = 4 * n * b
     fwd = 8 * nnz + 16 * n + 4 * n + 2 * act
-    bwd = 12 * nnz + 16 * n + 3 * act + (4 * nnz if fused else 0)
-    upd = (12 * nnz + 8 * n + act) if fused else (12 * nnz + 16 * n + 8 * n + 2 * act)
+    bwd = 12 * nnz + 16 * n + 3 * act
+    upd = (24 * nnz + 8 * n + act) if fused else (12 * nnz + 16 * n + 8 * n + 2 * act)
     return fwd, bwd, upd
 
 
@@ -79,17 +81,19 @@ def run_config(cfg, args, steps, warmup, headline):
 
     # ---- training step --------------------------------------------------
     t0 = time.time()
-    opts = dict(panel_cols=args.panel_cols) if headline else {}
+    opts = dict(panel_cols=args.panel_cols, fuse_gradient=args.fuse_gradient) if headline else {}
     net = sdnn.Net(work.layers, work.act_cap, Bt, training=True, **opts)
     torch.cuda.synchronize()
     create_s = time.time() - t0
     log(f"config {cfg}: training net created in {create_s:.1f} s, workspace {net.workspace_bytes / 2**30:.2f} GiB")
     # which kernels the library picks for this shape (its measured launch policy, restated here to name them):
-    # short rows and small layers run as two half-batches on two streams; wide layers (>= 16384 rows) with launches
+    # short rows and small layers run as two half-batches on two streams; layers of >= 4096 rows with launches
     # of at most 64 samples form the gradient in the backward sweep
     short_rows = nnz_total < 128 * N * L
     split = short_rows and Bt % 128 == 0 and N * Bt <= 2 ** 21
-    fused = short_rows and N >= 16384 and ((split and Bt == 128) or (not split and 1 < Bt <= 64))
+    fuse_opt = args.fuse_gradient if headline else 0
+    fused = (short_rows and (N >= 4096 or fuse_opt > 0) and fuse_opt >= 0
+             and ((split and Bt == 128) or (not split and 1 < Bt <= 64)))
     if split:
         v = 4 if Bt % 512 == 0 else 2 if Bt % 256 == 0 else 1
     else:
@@ -180,9 +184,10 @@ def run_config(cfg, args, steps, warmup, headline):
     first = work.layers[0]
     # separate backward: layers L..2 only; fused sweep: all layers, the first one without a Delta output
     bb -= (4 * first.n_in * Bt) if fused else layer_bytes(first.n_out, first.nnz, Bt, fused)[1]
-    kernels = {"forward": f"k_spmm<{v},0,{8 if short_rows else 16}>",
+    panels = short_rows and N * 256 >= (8 << 20) and (args.panel_cols >= 0 or not headline)   # the library's policy
+    kernels = {"forward": "k_spmm_panel<8,0>" if panels else f"k_spmm<{v},0,{8 if short_rows else 16}>",
                "backward": "k_bwd_grad<8>" if fused else f"k_spmm<{v},1,{8 if short_rows else 16}>",
-               "update": "k_apply + k_apply_bias" if fused else "k_update<4>"}
+               "update": "k_apply + k_gather_vals + k_apply_bias" if fused else "k_update<4>"}
     passes = {"forward": (fwd_ms, fb, L), "backward": (bwd_ms, bb, L if fused else L - 1), "update": (upd_ms, ub, 1)}
     dom = max(passes, key=lambda k: passes[k][0])
     d_ms, d_bytes, d_units = passes[dom]
@@ -338,6 +343,7 @@ def main():
     ap.add_argument("--reorder", choices=["both", "0", "1"], default="both",
                     help="--reorder-study: which settings of reorder_rows to run (one at a time for counter runs)")
     ap.add_argument("--panel-cols", type=int, default=0, help="sdnn_config.panel_cols of the headline nets and of --reorder-study (0 auto, -1 off)")
+    ap.add_argument("--fuse-gradient", type=int, default=0, help="sdnn_config.fuse_gradient of the headline training net (0 auto, 1 on, -1 off)")
     ap.add_argument("--lds-forward", type=int, default=0, help="sdnn_config.lds_forward of the headline inference net (0 auto, 1 on, -1 off)")
     ap.add_argument("--time-budget", type=float, default=400.0,
                     help="seconds since program start after which no further other_configs entry is begun")

@@ -171,7 +171,8 @@ struct SpmmArgs {
     int32_t act;
     const int32_t *n_live; // NULL, or the number of leading columns of the block that still matter (device)
     int32_t *flags;        // NULL, or MODE 0: flags[s] is set to 1 for every sample s with a non-zero output
-    float *g_part;         // GRAD kernels: gradient of the stored entries over this launch's samples, CSR order [nnz]
+    float *g_part;         // GRAD kernels: gradient of the stored entries over this launch's samples, in the order of
+                           // the transposed index [nnz]
     int32_t store_out;     // GRAD kernels: 0 = only the gradient is wanted (first layer: there is no Delta_0)
 };
 
@@ -647,12 +648,13 @@ __device__ __forceinline__ void spmm_row_grad(RowMeta m, const SpmmArgs &a, unsi
     xt[lane] = live ? xp : 0.0f;                    // samples outside the launch add nothing to the gradient
 
     double acc = 0.0;
-    int c_l = m.c_l, p_l = m.p_l;
+    int c_l = m.c_l, p_l;
     float w_l = m.w_l;
     const int e = lane & (GRAD_GE - 1), q = lane / GRAD_GE; // reducer of entry e over quarter q of the samples
     for (int base = m.beg; base < m.end; base += 64) {
         const int n = min(64, m.end - base);
-        if (base != m.beg) load_chunk<1>(a.idx, a.vals, a.perm, base, m.end, lane, c_l, w_l, p_l);
+        // a.vals is the copy of the values in the order of the transposed index: read like a forward row
+        if (base != m.beg) load_chunk<0>(a.idx, a.vals, nullptr, base, m.end, lane, c_l, w_l, p_l);
         for (int g0 = 0; g0 < n; g0 += GRAD_GE) { // GRAD_GE entries are parked at a time
             const int ng = min(GRAD_GE, n - g0);
             for (int g = 0; g < ng; g += U) {
@@ -703,8 +705,7 @@ __device__ __forceinline__ void spmm_row_grad(RowMeta m, const SpmmArgs &a, unsi
             }
             sum += __shfl_xor(sum, 16);
             sum += __shfl_xor(sum, 32);
-            const int pos = __shfl(p_l, g0 + e); // CSR position of entry e, held by lane g0 + e
-            if (q == 0 && e < ng) a.g_part[pos] = (float)sum;
+            if (q == 0 && e < ng) a.g_part[base + g0 + e] = (float)sum; // the entry's place in the transposed index
             wave_lds_sync(); // the next group's rows are parked over the ones just read
         }
     }
@@ -723,7 +724,7 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad(const SpmmArgs a)
         map_block(vb, a.n_tiles, a.n_rg, tile, rg);
         const int r = __builtin_amdgcn_readfirstlane((int)(rg * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
-        const RowMeta m = load_meta<1>(a.sched, a.idx, a.vals, a.perm, r, lane);
+        const RowMeta m = load_meta<0>(a.sched, a.idx, a.vals, nullptr, r, lane);
         spmm_row_grad<U>(m, a, tile + a.tile_base, lane, dt[wave], xt[wave]);
     }
 }
@@ -1049,27 +1050,60 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_apply(const LayerDev *__restrict__ layers, int n_parts, float lr)
 {
+    // The gradient and one copy of the values are in the order of the transposed index: this pass is a stream over
+    // both.  k_gather_vals then brings the CSR copy, which the forward pass reads, up to date.
     const LayerDev &L = layers[blockIdx.y];
     const double dlr = (double)lr;
     const float *__restrict__ g0 = L.G[0];
     const float *__restrict__ g1 = L.G[1];
-    float *__restrict__ vals = L.vals;
-    for (int p = blockIdx.x * 256 + threadIdx.x; p < L.nnz; p += gridDim.x * 256) {
-        double g = (double)g0[p];
-        if (n_parts == 2) g += (double)g1[p];
-        vals[p] = (float)((double)vals[p] - dlr * (double)(float)g);
+    float *__restrict__ vals_t = L.vals_t;
+    for (int q = blockIdx.x * 256 + threadIdx.x; q < L.nnz; q += gridDim.x * 256) {
+        double g = (double)g0[q];
+        if (n_parts == 2) g += (double)g1[q];
+        vals_t[q] = (float)((double)vals_t[q] - dlr * (double)(float)g);
     }
 }
 
-// The gradient that k_apply applies, for inspection: out = g0 (+ g1), the same rounding as in k_apply.
-__global__ void __launch_bounds__(256) k_sum_parts(const float *__restrict__ g0, const float *__restrict__ g1,
-                                                   float *__restrict__ out, int n)
+// vals[p] = vals_t[t_inv[p]]: the one random 4-byte access per entry and step that keeping the values in both
+// orders costs, taken as a read (random 4-byte stores into the CSR copy ran at half this rate).
+__global__ void __launch_bounds__(256) k_gather_vals(const LayerDev *__restrict__ layers)
 {
-    for (int p = blockIdx.x * 256 + threadIdx.x; p < n; p += gridDim.x * 256) {
-        double g = (double)g0[p];
-        if (g1) g += (double)g1[p];
-        out[p] = (float)g;
+    const LayerDev &L = layers[blockIdx.y];
+    const int32_t *__restrict__ inv = L.t_inv;
+    const float *__restrict__ vals_t = L.vals_t;
+    float *__restrict__ vals = L.vals;
+    const int n4 = L.nnz >> 2; // four consecutive entries per thread and trip: one index load, four gathers in flight
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < n4; t += gridDim.x * 256) {
+        const int4 i4 = reinterpret_cast<const int4 *>(inv)[t];
+        float4 v;
+        v.x = vals_t[i4.x]; v.y = vals_t[i4.y]; v.z = vals_t[i4.z]; v.w = vals_t[i4.w];
+        reinterpret_cast<float4 *>(vals)[t] = v;
     }
+    if (blockIdx.x == 0 && (int)threadIdx.x < (L.nnz & 3)) {
+        const int p = 4 * n4 + (int)threadIdx.x;
+        vals[p] = vals_t[inv[p]];
+    }
+}
+
+// The gradient that k_apply applies, for inspection, in CSR order: out[t_perm[q]] = g0[q] (+ g1[q]), the same
+// rounding as in k_apply.
+__global__ void __launch_bounds__(256) k_sum_parts(const float *__restrict__ g0, const float *__restrict__ g1,
+                                                   const int32_t *__restrict__ perm, float *__restrict__ out, int n)
+{
+    for (int q = blockIdx.x * 256 + threadIdx.x; q < n; q += gridDim.x * 256) {
+        double g = (double)g0[q];
+        if (g1) g += (double)g1[q];
+        out[perm[q]] = (float)g;
+    }
+}
+
+// vals_t[q] = vals[t_perm[q]]: brings the transposed-order copy of the values up to date after the CSR copy
+// was changed by something other than k_apply (sdnn_set_weights, the separate update kernel).
+__global__ void __launch_bounds__(256) k_refresh_vals_t(const LayerDev *__restrict__ layers)
+{
+    const LayerDev &L = layers[blockIdx.y];
+    if (!L.vals_t) return;
+    for (int q = blockIdx.x * 256 + threadIdx.x; q < L.nnz; q += gridDim.x * 256) L.vals_t[q] = L.vals[L.t_perm[q]];
 }
 
 // 16 lanes per row, four rows per wavefront at a time, 16 consecutive rows per wavefront.
@@ -1286,6 +1320,7 @@ struct sdnn_net {
     bool lds_ready = false;          // every layer has its lane-major copy (k_fwd_lds can run)
     bool lds_attr_set = false;       // the kernels' dynamic LDS limit has been raised
     int grad_parts = 0;           // > 0: the last backward pass left the entries' gradient in G[0..grad_parts)
+    bool vals_t_stale = false;    // the CSR values were changed by something that does not maintain vals_t
     hipStream_t side = nullptr;   // second stream for the other half of the batch (small layers)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int32_t *d_flags[2] = {nullptr, nullptr}, *d_map[2] = {nullptr, nullptr}, *d_n_live[2] = {nullptr, nullptr}; // inference: dead-sample skipping, two rounds' state
@@ -1350,7 +1385,7 @@ static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 // Workspace plan: offsets of every array, in one pass (also used to size it).
 struct Plan {
     struct PerLayer {
-        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2];
+        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2], vals_t, t_inv;
         size_t lm, lm_off, lm_row, lm_bias, lm_entries, lm_blocks;
     };
     std::vector<PerLayer> pl;
@@ -1394,7 +1429,7 @@ static bool grad_buffers_wanted(const sdnn_layer *layers, int32_t n_layers, cons
     if (cfg->fuse_gradient == SDNN_FUSE_ON) return true;
     int64_t rows = 0;
     for (int32_t l = 0; l < n_layers; ++l) rows += layers[l].n_out;
-    return rows >= (int64_t)16384 * n_layers;
+    return rows >= (int64_t)4096 * n_layers;
 }
 
 // The LDS-resident forward (k_fwd_lds) carries LDS_T samples through all layers with two activation
@@ -1449,7 +1484,7 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
         const sdnn_layer &y = layers[l];
         nnz[l] = (size_t)y.row_ptr[y.n_out];
         Plan::PerLayer &q = pl.pl[l];
-        q.X = q.D = q.G[0] = q.G[1] = 0;
+        q.X = q.D = q.G[0] = q.G[1] = q.vals_t = q.t_inv = 0;
         q.lm = q.lm_off = q.lm_row = q.lm_bias = q.lm_entries = q.lm_blocks = 0;
         if (lm) {
             std::vector<int32_t> lens;
@@ -1487,6 +1522,8 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
         if (gw) {
             PLAN_KIND(G[0], 4 * nnz[l])
             PLAN_KIND(G[1], 4 * nnz[l])
+            PLAN_KIND(vals_t, 4 * nnz[l])
+            PLAN_KIND(t_inv, 4 * nnz[l])
         }
     } else {
         pl.ping = take(4 * max_n * mb);
@@ -1569,6 +1606,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
     struct HostIdx {
         std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
         std::vector<int4> sched, t_sched;
+        std::vector<float> vals_t;
+        std::vector<int32_t> t_inv;
         std::vector<int2> lm;
         std::vector<int32_t> lm_off, lm_row;
         std::vector<float> lm_bias;
@@ -1577,6 +1616,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         int rc = SDNN_OK;
     };
     const bool want_lm = lds_forward_wanted(layers, n_layers, cfg);
+    const bool gw_ = grad_buffers_wanted(layers, n_layers, cfg);
     auto prepare = [&](int32_t l, HostIdx &h) {
         try {
             const sdnn_layer &y = layers[l];
@@ -1618,6 +1658,14 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 h.sched[r] = make_int4(h.order[r], y.row_ptr[h.order[r]], y.row_ptr[h.order[r] + 1], 0);
             for (int32_t r = 0; r < y.n_in; ++r)
                 h.t_sched[r] = make_int4(h.t_order[r], h.t_row_ptr[h.t_order[r]], h.t_row_ptr[h.t_order[r] + 1], 0);
+            if (gw_) { // the values in the order of the transposed index, for the fused backward sweep
+                h.vals_t.resize(nnz);
+                h.t_inv.resize(nnz);
+                for (size_t q = 0; q < nnz; ++q) {
+                    h.vals_t[q] = y.values[h.t_perm[q]];
+                    h.t_inv[(size_t)h.t_perm[q]] = (int32_t)q;
+                }
+            }
             if (want_lm) {
                 // lane-major copy: always in longest-first order, whatever the row schedule is
                 std::vector<int32_t> by_len((size_t)y.n_out);
@@ -1708,6 +1756,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 d.D = cfg->training ? (float *)(base + q.D) : nullptr;
                 d.G[0] = gw ? (float *)(base + q.G[0]) : nullptr;
                 d.G[1] = gw ? (float *)(base + q.G[1]) : nullptr;
+                d.vals_t = gw ? (float *)(base + q.vals_t) : nullptr;
+                d.t_inv = gw ? (const int32_t *)(base + q.t_inv) : nullptr;
                 d.lm = want_lm ? (int2 *)(base + q.lm) : nullptr;
                 d.lm_off = want_lm ? (const int32_t *)(base + q.lm_off) : nullptr;
                 d.lm_row = want_lm ? (const int32_t *)(base + q.lm_row) : nullptr;
@@ -1731,6 +1781,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 UP(d.t_perm, h.t_perm.data(), 4 * nnz);
                 UP(d.sched, h.sched.data(), 16 * (size_t)y.n_out);
                 UP(d.t_sched, h.t_sched.data(), 16 * (size_t)y.n_in);
+                if (gw) UP(d.vals_t, h.vals_t.data(), 4 * nnz);
+                if (gw) UP(d.t_inv, h.t_inv.data(), 4 * nnz);
                 if (want_lm) {
                     if (h.lm.size() != q.lm_entries)
                         return fail_free(fail(nullptr, SDNN_EINVAL, "layer %d: lane-major copy does not match its plan", l + 1));
@@ -2175,8 +2227,8 @@ static int launch_bwd_grad(sdnn_net *net, const LayerDev &d, float *out, int B, 
                            int store_out)
 {
     SpmmArgs a;
-    a.row_ptr = d.t_row_ptr; a.idx = d.t_row_idx; a.perm = d.t_perm; a.sched = d.t_sched; a.n_rows = d.n_in;
-    a.vals = d.vals; a.in = d.D; a.out = out; a.aux = d.X_prev; a.B = B; a.cap = net->cfg.act_cap;
+    a.row_ptr = d.t_row_ptr; a.idx = d.t_row_idx; a.perm = nullptr; a.sched = d.t_sched; a.n_rows = d.n_in;
+    a.vals = d.vals_t; a.in = d.D; a.out = out; a.aux = d.X_prev; a.B = B; a.cap = net->cfg.act_cap;
     a.act = net->cfg.activation; a.n_live = nullptr; a.flags = nullptr;
     a.g_part = d.G[part]; a.store_out = store_out;
     if (a.n_rows == 0 || d.nnz == 0) {
@@ -2236,6 +2288,17 @@ extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
     const int sv = split_v(net, B);
     const int gp = grad_fusable(net, B, sv);
     net->grad_parts = gp;
+    if (gp && net->vals_t_stale) { // the CSR values were replaced or stepped by the separate update since the last sweep
+        int max_nnz = 0;
+        for (const LayerDev &d : net->layers) max_nnz = std::max(max_nnz, d.nnz);
+        for (int l0 = 0; l0 < L && max_nnz > 0; l0 += 65535) {
+            const int nl = std::min(65535, L - l0);
+            hipLaunchKernelGGL(k_refresh_vals_t, dim3((unsigned)std::min(4096, (max_nnz + 2047) / 2048), (unsigned)nl), dim3(256), 0,
+                               stream, net->d_layers + l0);
+            HIP_TRY(net, hipGetLastError());
+        }
+        net->vals_t_stale = false;
+    }
     if (sv) {
         HIP_TRY(net, hipEventRecord(net->ev_fork, stream));
         HIP_TRY(net, hipStreamWaitEvent(net->side, net->ev_fork, 0));
@@ -2335,6 +2398,9 @@ extern "C" int sdnn_sgd_step(sdnn_net *net, float lr, void *stream_)
             if (max_nnz > 0) // 8 entries per thread
                 hipLaunchKernelGGL(k_apply, dim3((unsigned)std::min(4096, (max_nnz + 2047) / 2048), (unsigned)nl), dim3(256), 0,
                                    (hipStream_t)stream_, net->d_layers + l0, net->grad_parts, lr);
+            if (max_nnz > 0) // 4 entries per thread
+                hipLaunchKernelGGL(k_gather_vals, dim3((unsigned)std::min(8192, (max_nnz + 1023) / 1024), (unsigned)nl), dim3(256), 0,
+                                   (hipStream_t)stream_, net->d_layers + l0);
             if (max_rows > 0 && net->cfg.update_bias)
                 hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((max_rows + 16 * WAVES_PER_BLOCK - 1) / (16 * WAVES_PER_BLOCK)), (unsigned)nl),
                                    dim3(BLOCK_THREADS), 0, (hipStream_t)stream_, net->d_layers + l0, net->B, lr, (float *)nullptr);
@@ -2342,6 +2408,7 @@ extern "C" int sdnn_sgd_step(sdnn_net *net, float lr, void *stream_)
         }
     } else {
         rc = launch_update(net, 0, net->n_layers, lr, 0, nullptr, nullptr, (hipStream_t)stream_);
+        if (net->layers[0].vals_t) net->vals_t_stale = true; // this kernel steps the CSR copy only
     }
     if (rc) return rc;
     net->state = ST_IDLE;
@@ -2363,7 +2430,7 @@ extern "C" int sdnn_weight_grad(sdnn_net *net, int32_t layer, float *d_g, float 
         if (d_g && d.nnz > 0)
             hipLaunchKernelGGL(k_sum_parts, dim3((unsigned)std::min(4096, (d.nnz + 2047) / 2048)), dim3(256), 0, stream,
                                (const float *)d.G[0], net->grad_parts == 2 ? (const float *)d.G[1] : (const float *)nullptr,
-                               d_g, d.nnz);
+                               d.t_perm, d_g, d.nnz);
         if (d_gb && d.n_out > 0)
             hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((d.n_out + 16 * WAVES_PER_BLOCK - 1) / (16 * WAVES_PER_BLOCK)), 1u),
                                dim3(BLOCK_THREADS), 0, stream, net->d_layers + (layer - 1), net->B, 0.0f, d_gb);
@@ -2419,7 +2486,14 @@ extern "C" int sdnn_set_weights(sdnn_net *net, int32_t layer, const float *d_val
     if (layer < 1 || layer > net->n_layers) return fail(net, SDNN_EINVAL, "layer out of range");
     const LayerDev &d = net->layers[layer - 1];
     int rc = SDNN_OK;
-    if (d_values) rc = copy_dd(net, d.vals, d_values, 4 * (size_t)d.nnz, stream_);
+    if (d_values) {
+        rc = copy_dd(net, d.vals, d_values, 4 * (size_t)d.nnz, stream_);
+        if (!rc && d.vals_t && d.nnz > 0) { // the transposed-order copy follows at once
+            hipLaunchKernelGGL(k_refresh_vals_t, dim3((unsigned)std::min(4096, (d.nnz + 2047) / 2048), 1u), dim3(256), 0,
+                               (hipStream_t)stream_, net->d_layers + (layer - 1));
+            HIP_TRY(net, hipGetLastError());
+        }
+    }
     if (!rc && d_bias) {
         rc = copy_dd(net, d.bias, d_bias, 4 * (size_t)d.n_out, stream_);
         if (layer > 1) net->bias_nonpos = false; // device data: its signs are not inspected

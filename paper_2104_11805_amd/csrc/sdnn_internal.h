@@ -25,7 +25,11 @@ struct LayerDev {
     float *X_prev;            // X_{l-1}  [n_in][B]   (training mode)
     float *X;                 // X_l      [n_out][B]  (training mode)
     float *D;                 // Delta_l  [n_out][B]  (training mode)
-    float *G[2];              // [nnz] each: gradient of the stored entries over one half of the batch (training mode)
+    float *G[2];              // [nnz] each: gradient of the stored entries over one half of the batch, in the order of
+                              // the transposed index (fused backward sweep; training mode)
+    float *vals_t;            // [nnz]: the values in the order of the transposed index (vals_t[q] == vals[t_perm[q]]),
+                              // read by the fused backward sweep; NULL where that sweep is not set up
+    const int32_t *t_inv;     // [nnz]: the inverse of t_perm (t_inv[t_perm[q]] == q); NULL with vals_t
     // lane-major copy of W for the LDS-resident forward (small inference nets; NULL otherwise): the rows,
     // longest first, in blocks of 64; block b holds, for k = 0 .. K_b - 1, entry k of its 64 rows side by
     // side (lm[lm_off[b] + 64 k + lane] = {column, weight bits}), padded with {0, 0.0f} up to the block's
