@@ -92,10 +92,12 @@ typedef struct {
 
 /* Where the batch allows it (at most 64 samples per launch, short rows), sdnn_backward can form
  * the gradient of the stored entries (Eq. 4) in the same sweep that back-propagates through W_l
- * (Eq. 7): both need the rows of Delta_l that an entry points at.  sdnn_sgd_step is then a
- * streaming pass.  Same results within the rounding of the sum over samples; costs 8 more bytes
- * of workspace per stored entry.  AUTO turns it on for wide layers (mean n_out >= 16384), where
- * it is faster. */
+ * (Eq. 7): both need the rows of Delta_l that an entry points at.  The net then keeps the values a
+ * second time, in the order of the transposed index, which that sweep reads in a stream; the
+ * gradient is left in the same order, sdnn_sgd_step is a streaming pass over both and rebuilds the
+ * CSR copy in a second pass that moves whole runs of entries.  Same results within the rounding of
+ * the sum over samples; costs 24 more bytes of workspace per stored entry.  AUTO turns it on for
+ * nets with short rows whose layers have 4096 rows or more on average, where it is faster. */
 #define SDNN_FUSE_AUTO 0
 #define SDNN_FUSE_ON 1
 #define SDNN_FUSE_OFF (-1)

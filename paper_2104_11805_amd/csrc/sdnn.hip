@@ -629,6 +629,9 @@ __global__ void __launch_bounds__(64) k_lm_refresh(const LayerDev *__restrict__ 
 // the whole gradient array; nothing is accumulated in memory.  This removes the update's own
 // gather pass over X_{l-1}.
 // ---------------------------------------------------------------------------
+#define TR_CHUNK 16384 // entries of the CSR array that one workgroup of k_spread_vals fills from LDS (64 KiB)
+#define TR_THREADS 512
+#define TR_SPAN 8192   // consecutive entries of the transposed index that one workgroup of k_apply takes (32 KiB of LDS)
 #define GRAD_LD 68 // floats per parked entry: 64 samples + pad (rows stay 16-byte aligned, banks spread)
 #define GRAD_GE 16 // entries parked at a time: 4.6 KB of LDS per wavefront, which keeps 8 wavefronts per SIMD
 template <int U>
@@ -1048,41 +1051,74 @@ k_update(const LayerDev *__restrict__ layers, int layer0, int n_layers, int inte
 // over the entries of every layer (grid = (chunks of entries, layers)); k_apply_bias forms the bias
 // gradient sum_s Delta(row, s).
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_apply(const LayerDev *__restrict__ layers, int n_parts, float lr)
+__global__ void __launch_bounds__(TR_THREADS) k_apply(const LayerDev *__restrict__ layers, int n_parts, float lr)
 {
     // The gradient and one copy of the values are in the order of the transposed index: this pass is a stream over
-    // both.  k_gather_vals then brings the CSR copy, which the forward pass reads, up to date.
+    // both.  The new values also go to `mid`, grouped by the chunk of the CSR array they belong to: a workgroup
+    // takes a span of TR_SPAN consecutive entries, puts the new values into the order they have in mid in LDS
+    // (mid_slot) and stores them from there, neighbouring threads into neighbouring places of a run (mid_dst).
+    // k_spread_vals then fills the CSR copy, which the forward pass reads, chunk by chunk.  The workgroups of
+    // one XCD take neighbouring spans, so that the pieces of a cache line of mid meet in one L2.
+    __shared__ __attribute__((aligned(16))) float stage[TR_SPAN];
     const LayerDev &L = layers[blockIdx.y];
+    const int nb = (int)gridDim.x; // a multiple of 8
+    const int vb = ((int)blockIdx.x & 7) * (nb >> 3) + ((int)blockIdx.x >> 3);
+    const int64_t q0 = (int64_t)vb * TR_SPAN;
+    if (q0 >= L.nnz) return;
+    const int cnt = (int)min((int64_t)TR_SPAN, (int64_t)L.nnz - q0), cnt4 = cnt >> 2;
     const double dlr = (double)lr;
-    const float *__restrict__ g0 = L.G[0];
-    const float *__restrict__ g1 = L.G[1];
-    float *__restrict__ vals_t = L.vals_t;
-    for (int q = blockIdx.x * 256 + threadIdx.x; q < L.nnz; q += gridDim.x * 256) {
-        double g = (double)g0[q];
-        if (n_parts == 2) g += (double)g1[q];
-        vals_t[q] = (float)((double)vals_t[q] - dlr * (double)(float)g);
+    const float *__restrict__ g0 = L.G[0] + q0;
+    const float *__restrict__ g1 = L.G[1] + q0;
+    const uint16_t *__restrict__ slot = L.mid_slot + q0;
+    const int32_t *__restrict__ dst = L.mid_dst + q0;
+    float *__restrict__ vals_t = L.vals_t + q0;
+    float *__restrict__ mid = L.mid;
+    const int tid = (int)threadIdx.x;
+#define APPLY_ONE(G0, G1, W) (float)((double)(W) - dlr * (double)(float)(n_parts == 2 ? (double)(G0) + (double)(G1) : (double)(G0)))
+    for (int k = tid; k < cnt4; k += TR_THREADS) { // q0 is a multiple of 4 and the arrays are 16-byte aligned
+        const float4 a = reinterpret_cast<const float4 *>(g0)[k];
+        float4 b = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (n_parts == 2) b = reinterpret_cast<const float4 *>(g1)[k];
+        float4 w = reinterpret_cast<const float4 *>(vals_t)[k];
+        const ushort4 o = reinterpret_cast<const ushort4 *>(slot)[k];
+        w.x = APPLY_ONE(a.x, b.x, w.x); w.y = APPLY_ONE(a.y, b.y, w.y);
+        w.z = APPLY_ONE(a.z, b.z, w.z); w.w = APPLY_ONE(a.w, b.w, w.w);
+        reinterpret_cast<float4 *>(vals_t)[k] = w;
+        stage[o.x] = w.x; stage[o.y] = w.y; stage[o.z] = w.z; stage[o.w] = w.w;
     }
+    if (tid < (cnt & 3)) {
+        const int k = 4 * cnt4 + tid;
+        const float w = APPLY_ONE(g0[k], n_parts == 2 ? g1[k] : 0.0f, vals_t[k]);
+        vals_t[k] = w;
+        stage[slot[k]] = w;
+    }
+#undef APPLY_ONE
+    __syncthreads();
+    for (int k = tid; k < cnt; k += TR_THREADS) mid[dst[k]] = stage[k];
 }
 
-// vals[p] = vals_t[t_inv[p]]: the one random 4-byte access per entry and step that keeping the values in both
-// orders costs, taken as a read (random 4-byte stores into the CSR copy ran at half this rate).
-__global__ void __launch_bounds__(256) k_gather_vals(const LayerDev *__restrict__ layers)
+// Chunk c of the CSR values from entries [c TR_CHUNK, (c+1) TR_CHUNK) of mid: placed in LDS by mid_loc, then
+// written out in order.  grid = (chunks, layers).
+__global__ void __launch_bounds__(TR_THREADS) k_spread_vals(const LayerDev *__restrict__ layers)
 {
+    __shared__ __attribute__((aligned(16))) float chunk[TR_CHUNK];
     const LayerDev &L = layers[blockIdx.y];
-    const int32_t *__restrict__ inv = L.t_inv;
-    const float *__restrict__ vals_t = L.vals_t;
-    float *__restrict__ vals = L.vals;
-    const int n4 = L.nnz >> 2; // four consecutive entries per thread and trip: one index load, four gathers in flight
-    for (int t = blockIdx.x * 256 + threadIdx.x; t < n4; t += gridDim.x * 256) {
-        const int4 i4 = reinterpret_cast<const int4 *>(inv)[t];
-        float4 v;
-        v.x = vals_t[i4.x]; v.y = vals_t[i4.y]; v.z = vals_t[i4.z]; v.w = vals_t[i4.w];
-        reinterpret_cast<float4 *>(vals)[t] = v;
+    const int64_t c0 = (int64_t)blockIdx.x * TR_CHUNK;
+    if (c0 >= L.nnz) return;
+    const int cnt = (int)min((int64_t)TR_CHUNK, (int64_t)L.nnz - c0), cnt4 = cnt >> 2;
+    const float *__restrict__ mid = L.mid + c0;
+    const uint16_t *__restrict__ loc = L.mid_loc + c0;
+    float *__restrict__ vals = L.vals + c0;
+    for (int k = (int)threadIdx.x; k < cnt4; k += TR_THREADS) { // c0 is a multiple of 4 and the arrays are 16-byte aligned
+        const float4 v = reinterpret_cast<const float4 *>(mid)[k];
+        const ushort4 o = reinterpret_cast<const ushort4 *>(loc)[k];
+        chunk[o.x] = v.x; chunk[o.y] = v.y; chunk[o.z] = v.z; chunk[o.w] = v.w;
     }
-    if (blockIdx.x == 0 && (int)threadIdx.x < (L.nnz & 3)) {
-        const int p = 4 * n4 + (int)threadIdx.x;
-        vals[p] = vals_t[inv[p]];
-    }
+    if ((int)threadIdx.x < (cnt & 3)) chunk[loc[4 * cnt4 + (int)threadIdx.x]] = mid[4 * cnt4 + (int)threadIdx.x];
+    __syncthreads();
+    for (int k = (int)threadIdx.x; k < cnt4; k += TR_THREADS)
+        reinterpret_cast<float4 *>(vals)[k] = reinterpret_cast<const float4 *>(chunk)[k];
+    if ((int)threadIdx.x < (cnt & 3)) vals[4 * cnt4 + (int)threadIdx.x] = chunk[4 * cnt4 + (int)threadIdx.x];
 }
 
 // The gradient that k_apply applies, for inspection, in CSR order: out[t_perm[q]] = g0[q] (+ g1[q]), the same
@@ -1385,7 +1421,7 @@ static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 // Workspace plan: offsets of every array, in one pass (also used to size it).
 struct Plan {
     struct PerLayer {
-        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2], vals_t, t_inv;
+        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2], vals_t, mid_slot, mid_dst, mid_loc, mid;
         size_t lm, lm_off, lm_row, lm_bias, lm_entries, lm_blocks;
     };
     std::vector<PerLayer> pl;
@@ -1420,16 +1456,20 @@ static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_c
     return SDNN_OK;
 }
 
-// The fused backward + gradient kernels pay on wide layers, whose launches are bound by gather
-// throughput; on narrow ones, bound by the latency of a launch, the separate update is faster
-// (measured step time: 4096 rows +5 %, 16384 rows -2 %, 65536 rows -16 %).
+// The fused backward + gradient kernels pay from layers of 4096 rows on, whose launches are bound by gather
+// throughput; below that, where the latency of a launch binds, the separate update is faster (measured step
+// time against the separate kernels: 1024 rows +10 %, 4096 rows -5 %, 16384 rows -20 %, 65536 rows -30 %).
+// Nets with long rows never take the fused kernels (grad_fusable), so AUTO sets nothing up for them.
 static bool grad_buffers_wanted(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg)
 {
     if (!cfg->training || cfg->fuse_gradient == SDNN_FUSE_OFF) return false;
     if (cfg->fuse_gradient == SDNN_FUSE_ON) return true;
-    int64_t rows = 0;
-    for (int32_t l = 0; l < n_layers; ++l) rows += layers[l].n_out;
-    return rows >= (int64_t)4096 * n_layers;
+    int64_t rows = 0, nnz = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        rows += layers[l].n_out;
+        nnz += layers[l].row_ptr ? layers[l].row_ptr[layers[l].n_out] : 0;
+    }
+    return rows >= (int64_t)4096 * n_layers && nnz < 128 * rows;
 }
 
 // The LDS-resident forward (k_fwd_lds) carries LDS_T samples through all layers with two activation
@@ -1484,7 +1524,7 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
         const sdnn_layer &y = layers[l];
         nnz[l] = (size_t)y.row_ptr[y.n_out];
         Plan::PerLayer &q = pl.pl[l];
-        q.X = q.D = q.G[0] = q.G[1] = q.vals_t = q.t_inv = 0;
+        q.X = q.D = q.G[0] = q.G[1] = q.vals_t = q.mid_slot = q.mid_dst = q.mid_loc = q.mid = 0;
         q.lm = q.lm_off = q.lm_row = q.lm_bias = q.lm_entries = q.lm_blocks = 0;
         if (lm) {
             std::vector<int32_t> lens;
@@ -1523,7 +1563,10 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
             PLAN_KIND(G[0], 4 * nnz[l])
             PLAN_KIND(G[1], 4 * nnz[l])
             PLAN_KIND(vals_t, 4 * nnz[l])
-            PLAN_KIND(t_inv, 4 * nnz[l])
+            PLAN_KIND(mid_slot, 2 * nnz[l])
+            PLAN_KIND(mid_dst, 4 * nnz[l])
+            PLAN_KIND(mid_loc, 2 * nnz[l])
+            PLAN_KIND(mid, 4 * nnz[l])
         }
     } else {
         pl.ping = take(4 * max_n * mb);
@@ -1607,7 +1650,8 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         std::vector<int32_t> t_row_ptr, t_row_idx, t_perm, order, t_order;
         std::vector<int4> sched, t_sched;
         std::vector<float> vals_t;
-        std::vector<int32_t> t_inv;
+        std::vector<int32_t> mid_dst;
+        std::vector<uint16_t> mid_slot, mid_loc;
         std::vector<int2> lm;
         std::vector<int32_t> lm_off, lm_row;
         std::vector<float> lm_bias;
@@ -1660,10 +1704,32 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 h.t_sched[r] = make_int4(h.t_order[r], h.t_row_ptr[h.t_order[r]], h.t_row_ptr[h.t_order[r] + 1], 0);
             if (gw_) { // the values in the order of the transposed index, for the fused backward sweep
                 h.vals_t.resize(nnz);
-                h.t_inv.resize(nnz);
-                for (size_t q = 0; q < nnz; ++q) {
-                    h.vals_t[q] = y.values[h.t_perm[q]];
-                    h.t_inv[(size_t)h.t_perm[q]] = (int32_t)q;
+                h.mid_slot.resize(nnz);
+                h.mid_dst.resize(nnz);
+                h.mid_loc.resize(nnz);
+                // every chunk of the CSR array but the last holds TR_CHUNK entries, so chunk c's group starts at c TR_CHUNK
+                const size_t n_chunks = (nnz + TR_CHUNK - 1) / TR_CHUNK;
+                std::vector<int32_t> filled(n_chunks, 0), in_span(n_chunks, 0), touched;
+                for (size_t s0 = 0; s0 < nnz; s0 += TR_SPAN) {
+                    const size_t s1 = std::min(nnz, s0 + (size_t)TR_SPAN);
+                    touched.clear();
+                    for (size_t q = s0; q < s1; ++q) {
+                        const size_t c = (size_t)h.t_perm[q] / TR_CHUNK;
+                        if (in_span[c]++ == 0) touched.push_back((int32_t)c);
+                    }
+                    std::sort(touched.begin(), touched.end());
+                    int32_t run = 0; // in_span[c]: from the span's count for chunk c to the rank of its next entry
+                    for (int32_t c : touched) { const int32_t n = in_span[c]; in_span[c] = run; run += n; }
+                    for (size_t q = s0; q < s1; ++q) {
+                        const size_t p = (size_t)h.t_perm[q], c = p / TR_CHUNK;
+                        const size_t m = c * TR_CHUNK + (size_t)filled[c]++;
+                        const int32_t k = in_span[c]++;
+                        h.vals_t[q] = y.values[p];
+                        h.mid_slot[q] = (uint16_t)k;
+                        h.mid_dst[s0 + (size_t)k] = (int32_t)m;
+                        h.mid_loc[m] = (uint16_t)(p - c * TR_CHUNK);
+                    }
+                    for (int32_t c : touched) in_span[c] = 0;
                 }
             }
             if (want_lm) {
@@ -1757,7 +1823,10 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 d.G[0] = gw ? (float *)(base + q.G[0]) : nullptr;
                 d.G[1] = gw ? (float *)(base + q.G[1]) : nullptr;
                 d.vals_t = gw ? (float *)(base + q.vals_t) : nullptr;
-                d.t_inv = gw ? (const int32_t *)(base + q.t_inv) : nullptr;
+                d.mid_slot = gw ? (const uint16_t *)(base + q.mid_slot) : nullptr;
+                d.mid_dst = gw ? (const int32_t *)(base + q.mid_dst) : nullptr;
+                d.mid_loc = gw ? (const uint16_t *)(base + q.mid_loc) : nullptr;
+                d.mid = gw ? (float *)(base + q.mid) : nullptr;
                 d.lm = want_lm ? (int2 *)(base + q.lm) : nullptr;
                 d.lm_off = want_lm ? (const int32_t *)(base + q.lm_off) : nullptr;
                 d.lm_row = want_lm ? (const int32_t *)(base + q.lm_row) : nullptr;
@@ -1782,7 +1851,9 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 UP(d.sched, h.sched.data(), 16 * (size_t)y.n_out);
                 UP(d.t_sched, h.t_sched.data(), 16 * (size_t)y.n_in);
                 if (gw) UP(d.vals_t, h.vals_t.data(), 4 * nnz);
-                if (gw) UP(d.t_inv, h.t_inv.data(), 4 * nnz);
+                if (gw) UP(d.mid_slot, h.mid_slot.data(), 2 * nnz);
+                if (gw) UP(d.mid_dst, h.mid_dst.data(), 4 * nnz);
+                if (gw) UP(d.mid_loc, h.mid_loc.data(), 2 * nnz);
                 if (want_lm) {
                     if (h.lm.size() != q.lm_entries)
                         return fail_free(fail(nullptr, SDNN_EINVAL, "layer %d: lane-major copy does not match its plan", l + 1));
@@ -2395,12 +2466,13 @@ extern "C" int sdnn_sgd_step(sdnn_net *net, float lr, void *stream_)
         for (const LayerDev &d : net->layers) { max_rows = std::max(max_rows, d.n_out); max_nnz = std::max(max_nnz, d.nnz); }
         for (int l0 = 0; l0 < net->n_layers; l0 += 65535) {
             const int nl = std::min(65535, net->n_layers - l0);
-            if (max_nnz > 0) // 8 entries per thread
-                hipLaunchKernelGGL(k_apply, dim3((unsigned)std::min(4096, (max_nnz + 2047) / 2048), (unsigned)nl), dim3(256), 0,
-                                   (hipStream_t)stream_, net->d_layers + l0, net->grad_parts, lr);
-            if (max_nnz > 0) // 4 entries per thread
-                hipLaunchKernelGGL(k_gather_vals, dim3((unsigned)std::min(8192, (max_nnz + 1023) / 1024), (unsigned)nl), dim3(256), 0,
-                                   (hipStream_t)stream_, net->d_layers + l0);
+            if (max_nnz > 0) { // a span per workgroup, a multiple of 8 workgroups per layer
+                const unsigned gx = (unsigned)((((int64_t)max_nnz + TR_SPAN - 1) / TR_SPAN + 7) & ~(int64_t)7);
+                hipLaunchKernelGGL(k_apply, dim3(gx, (unsigned)nl), dim3(TR_THREADS), 0, (hipStream_t)stream_,
+                                   net->d_layers + l0, net->grad_parts, lr);
+                hipLaunchKernelGGL(k_spread_vals, dim3((unsigned)((max_nnz + TR_CHUNK - 1) / TR_CHUNK), (unsigned)nl),
+                                   dim3(TR_THREADS), 0, (hipStream_t)stream_, net->d_layers + l0);
+            }
             if (max_rows > 0 && net->cfg.update_bias)
                 hipLaunchKernelGGL(k_apply_bias, dim3((unsigned)((max_rows + 16 * WAVES_PER_BLOCK - 1) / (16 * WAVES_PER_BLOCK)), (unsigned)nl),
                                    dim3(BLOCK_THREADS), 0, (hipStream_t)stream_, net->d_layers + l0, net->B, lr, (float *)nullptr);

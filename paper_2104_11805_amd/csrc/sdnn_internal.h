@@ -29,7 +29,15 @@ struct LayerDev {
                               // the transposed index (fused backward sweep; training mode)
     float *vals_t;            // [nnz]: the values in the order of the transposed index (vals_t[q] == vals[t_perm[q]]),
                               // read by the fused backward sweep; NULL where that sweep is not set up
-    const int32_t *t_inv;     // [nnz]: the inverse of t_perm (t_inv[t_perm[q]] == q); NULL with vals_t
+    // The way back from the transposed order to the CSR order, in two passes that both move whole runs (NULL with
+    // vals_t).  `mid` holds the values grouped by the TR_CHUNK-entry chunk of the CSR array they belong to, inside
+    // a chunk in the order of the transposed index, so that chunk c of the CSR array is filled from entries
+    // [c TR_CHUNK, (c+1) TR_CHUNK) of mid.  A span of TR_SPAN consecutive entries of the transposed index lands
+    // in mid as one run per chunk; the span's workgroup first puts its values into that order in LDS.
+    const uint16_t *mid_slot; // [nnz]: rank of entry q among the entries of its span, by place in mid
+    const int32_t *mid_dst;   // [nnz]: mid_dst[span start + k] = the place in mid of the span's entry of rank k
+    const uint16_t *mid_loc;  // [nnz]: t_perm of the entry at that place of mid, minus its chunk's start
+    float *mid;               // [nnz]
     // lane-major copy of W for the LDS-resident forward (small inference nets; NULL otherwise): the rows,
     // longest first, in blocks of 64; block b holds, for k = 0 .. K_b - 1, entry k of its 64 rows side by
     // side (lm[lm_off[b] + 64 k + lane] = {column, weight bits}), padded with {0, 0.0f} up to the block's
