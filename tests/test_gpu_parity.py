@@ -424,28 +424,32 @@ def test_uniform_rows_wide_batches(n, d, b, training):
 @pytest.mark.parametrize("b", [64, 128, 17])
 def test_fused_gradient_layout_over_several_steps(b):
     """The fused sweep keeps the values a second time, in the order of the transposed index, and the step writes
-    both copies: layers of 31521, 69286 and 39647 entries (several spans and chunks of the way back to the CSR order, none
-    a multiple of four), three steps with the weights carried over, one layer's weights replaced before the last
-    step.  After every step the forward pass (CSR copy), the deltas (transposed copy) and the gradient handed out
-    in CSR order must all be the oracle's."""
+    both copies: layers of 31521, 69286 and 39647 entries (several spans and chunks of the way back to the CSR order,
+    none a multiple of four), four steps with the weights carried over: fused, then a batch of 100 (not fusable: the
+    separate update steps the CSR copy only and the next sweep must bring the other copy up to date), fused again,
+    and fused after one layer's weights were replaced.  After every step the forward pass (CSR copy), the deltas
+    (transposed copy) and the gradient handed out in CSR order must all be the oracle's."""
     sizes = (900, 700, 1100, 600)
     layers = [wl.random_layer(8130 + l, sizes[l + 1], sizes[l], (0.05, 0.09, 0.06)[l], scale=0.3) for l in range(3)]
     assert all(l.nnz > 3 * 8192 and l.nnz % 4 for l in layers) and max(l.nnz for l in layers) > 4 * 16384
-    x = wl.normal_inputs(8190, sizes[0], 3 * b)
-    tg = wl.uniform_targets(8191, sizes[-1], 3 * b)
+    batches = [b, 100, b, b]
+    x = wl.normal_inputs(8190, sizes[0], sum(batches))
+    tg = wl.uniform_targets(8191, sizes[-1], sum(batches))
     work = wl.Workload("fused-layout", layers, 4.0, x, b, "mse", 0.05, targets=tg)
-    net = sdnn.Net(layers, work.act_cap, b, training=True, fuse_gradient=1)
-    for s in range(3):
-        x0 = np.ascontiguousarray(x[:, s * b:(s + 1) * b])
-        y = np.ascontiguousarray(tg[:, s * b:(s + 1) * b])
-        if s == 2:      # new values for layer 2: both copies must follow
+    net = sdnn.Net(layers, work.act_cap, 128, training=True, fuse_gradient=1)
+    at = 0
+    for s, bs in enumerate(batches):
+        x0 = np.ascontiguousarray(x[:, at:at + bs])
+        y = np.ascontiguousarray(tg[:, at:at + bs])
+        at += bs
+        if s == 3:      # new values for layer 2: both copies must follow
             rng = np.random.default_rng(8199)
             layers[1].values = (layers[1].values * rng.uniform(0.5, 1.5, layers[1].nnz)).astype(np.float32)
             net.sdnn_set_weights(2, P.dev(layers[1].values), P.dev(layers[1].bias))
-        xl = torch.empty(sizes[-1], b, device=P.DEV)
+        xl = torch.empty(sizes[-1], bs, device=P.DEV)
         net.sdnn_forward(P.dev(x0), xl)
         net.sdnn_backward(sdnn.sdnn_mse_dloss(xl, P.dev(y)))
-        got_d = [P.host(net.sdnn_get_delta(k, b)) for k in range(1, 4)]
+        got_d = [P.host(net.sdnn_get_delta(k, bs)) for k in range(1, 4)]
         got_g = [tuple(P.host(t) for t in net.sdnn_weight_grad(k)) for k in range(1, 4)]
         net.sdnn_sgd_step(work.lr)
         xs, deltas, grads, new = P.O32.train_step(layers, x0, work.act_cap, lambda v: P.mse_dloss(v, y), work.lr)
