@@ -464,3 +464,48 @@ def test_fused_gradient_layout_over_several_steps(b):
             assert (new[k][0] != layers[k].values).any()
             layers[k].values, layers[k].bias = gv, gb      # both sides go on from the GPU's weights: bits stay comparable
     net.close()
+
+
+def test_fused_gradient_layout_at_the_sizes_of_its_spans_and_chunks():
+    """Entry counts at the edges of the way back to the CSR order: exactly one span (8192), exactly one chunk
+    (16384), five entries, none (a layer without entries sends only f(bias) on and no delta back), and just over a chunk.
+    Two steps, so that the second one reads the values the first one wrote."""
+    rng = np.random.default_rng(8300)
+
+    def with_random_weights(lay, scale):
+        lay.values = (rng.standard_normal(lay.nnz) * scale).astype(np.float32)
+        lay.bias = (rng.standard_normal(lay.n_out) * 0.3).astype(np.float32)
+        return lay
+
+    few = wl.random_layer(8303, 64, 512, 0.0001, scale=0.5)
+    few.bias = np.abs(few.bias) + 0.1          # its outputs stay alive without inputs
+    none = wl.random_layer(8304, 96, 64, 0.0, scale=0.5)
+    none.bias = np.abs(none.bias) + 0.1
+    last = wl.random_layer(8305, 173, 96, 0.99, scale=0.2)
+    layers = [with_random_weights(wl.regular_layer(8301, 256, 32, 0.0, 0.0), 0.3),
+              with_random_weights(wl.regular_layer(8302, 512, 32, 0.0, 0.0, n_in=256), 0.3), few, none, last]
+    wide = wl.random_layer(8306, 300, 173, 0.3158, scale=0.2)
+    layers.append(wide)
+    assert [l.nnz for l in layers[:4]] == [8192, 16384, 5, 0] and layers[5].nnz in range(16385, 16500)
+    b = 64
+    x = wl.normal_inputs(8390, 256, 2 * b)
+    tg = wl.uniform_targets(8391, 300, 2 * b)
+    net = sdnn.Net(layers, 4.0, b, training=True, fuse_gradient=1)
+    for s in range(2):
+        x0 = np.ascontiguousarray(x[:, s * b:(s + 1) * b])
+        y = np.ascontiguousarray(tg[:, s * b:(s + 1) * b])
+        xl = torch.empty(300, b, device=P.DEV)
+        net.sdnn_forward(P.dev(x0), xl)
+        net.sdnn_backward(sdnn.sdnn_mse_dloss(xl, P.dev(y)))
+        got_d = [P.host(net.sdnn_get_delta(k, b)) for k in range(1, 7)]
+        net.sdnn_sgd_step(0.05)
+        xs, deltas, grads, new = P.O32.train_step(layers, x0, 4.0, lambda v: P.mse_dloss(v, y), 0.05)
+        assert np.array_equal(P.host(xl), xs[-1]), f"step {s}: X_L"
+        for k in range(6):
+            assert np.array_equal(got_d[k], deltas[k + 1]), f"step {s}: delta {k + 1}"
+            gv, gb = (P.host(t) for t in net.sdnn_get_weights(k + 1))
+            P.assert_grad_close(gv, new[k][0], f"step {s} layer {k + 1} weights")
+            P.assert_grad_close(gb, new[k][1], f"step {s} layer {k + 1} bias")
+            layers[k].values, layers[k].bias = gv, gb
+        assert (deltas[5] != 0).any() and (deltas[6] != 0).any()
+    net.close()
