@@ -160,3 +160,24 @@ def test_lds_resident_forward_benchmark_nets_and_replaced_weights():
     net.sdnn_forward(P.dev(x), out)
     assert np.array_equal(P.host(out), P.O32.forward(wide, x, 32.0)[-1])
     net.close()
+
+
+@pytest.mark.parametrize("n,b,opts", [(4096, 2304, dict(lds_forward=-1)),            # sub-blocks of 1024, 1024, 256
+                                     (24576, 448, dict(panel_cols=4096)),           # panel sweep throughout: 128, 128, 128, 64
+                                     (24576, 448, dict(panel_cols=-1))])            # 256, 192
+def test_inference_in_sub_blocks_of_samples(n, b, opts):
+    """Activation blocks of more than 32 MiB are taken through all layers in sub-blocks of samples (what a layer
+    wrote is still on chip when the next one gathers it): every column of the result must be the oracle's."""
+    layers = [wl.regular_layer(8400 + l, n, 32, 0.0625, -0.3) for l in range(3)]
+    rng = np.random.default_rng(8410)
+    for l in layers:
+        l.values = (l.values * rng.uniform(0.5, 1.5, l.nnz)).astype(np.float32)
+    assert 4 * n * b > 32 * 2 ** 20
+    x = wl.binary_inputs(8411, n, b, 0.4)
+    ref = P.O32.forward(layers, x, 32.0)[-1]
+    assert 0.2 < (ref > 0).mean() and (ref < 32.0).mean() > 0.2
+    net = sdnn.Net(layers, 32.0, b, training=False, **opts)
+    out = torch.full((n, b), -1.0, device=P.DEV)
+    net.sdnn_forward(P.dev(x), out)
+    assert np.array_equal(P.host(out), ref)
+    net.close()
