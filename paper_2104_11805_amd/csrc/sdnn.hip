@@ -11,11 +11,16 @@
 //   * pattern-confined gradient: one wavefront per row, lanes split as
 //     4 edge groups x 16 sample lanes, so that only a 16-lane butterfly is
 //     needed per 8 edges before the weight is rewritten in place.
-//   * W^T is never stored: the transposed index lists, per column, the source
-//     rows and the positions of the values in the CSR array.
-//   * wide layers: the backward sweep also forms the gradient of the stored
-//     entries (k_bwd_grad, gathered rows parked in LDS), the descent step is
-//     then a streaming pass (k_apply).
+//   * W^T: the transposed index lists, per column, the source rows and the
+//     positions of the values in the CSR array.
+//   * layers of 4096 rows and more: the backward sweep also forms the gradient
+//     of the stored entries (k_bwd_grad, gathered rows parked in LDS) and reads
+//     the values from a copy in the order of the transposed index; the descent
+//     step is then a streaming pass over that copy (k_apply) and a second one
+//     that rebuilds the CSR copy (k_spread_vals).
+//   * inference on large activation blocks goes through all layers in
+//     sub-blocks of samples, so that a layer's output is still in the
+//     memory-side cache when the next layer gathers it.
 //   * one sample per step (B = 1): lanes over entries / rows instead of samples
 //     (k_spmv_stage, k_spmv_wave, k_spmv, k_update_b1).
 //   * inference that drops dead samples: flags set by the forward epilogue,
@@ -625,9 +630,10 @@ __global__ void __launch_bounds__(64) k_lm_refresh(const LayerDev *__restrict__ 
 // Eq. 4 for exactly that entry.  The gathered rows are parked in LDS, 16 entries at a time
 // ([entry][sample], padded), and then lane (e, q) sums entry e over quarter q of the samples in fp64;
 // the four quarters are added and lane e stores g(j, i) = sum_s Delta_l(j, s) X_{l-1}(i, s) at the
-// entry's CSR position.  Every stored entry lies in exactly one row of W_l^T, so the launch writes
-// the whole gradient array; nothing is accumulated in memory.  This removes the update's own
-// gather pass over X_{l-1}.
+// entry's place in the transposed index.  Every stored entry lies in exactly one row of W_l^T, so the
+// launch writes the whole gradient array; nothing is accumulated in memory.  The values are read from
+// their copy in the same order (vals_t): the sweep streams through index, values and gradient, and
+// only the rows of Delta_l are gathered.  This removes the update's own gather pass over X_{l-1}.
 // ---------------------------------------------------------------------------
 #define TR_CHUNK 16384 // entries of the CSR array that one workgroup of k_spread_vals fills from LDS (64 KiB)
 #define TR_THREADS 512
