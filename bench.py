@@ -87,13 +87,14 @@ def run_config(cfg, args, steps, warmup, headline):
     create_s = time.time() - t0
     log(f"config {cfg}: training net created in {create_s:.1f} s, workspace {net.workspace_bytes / 2**30:.2f} GiB")
     # which kernels the library picks for this shape (its measured launch policy, restated here to name them):
-    # short rows and small layers run as two half-batches on two streams; layers of >= 4096 rows with launches
-    # of at most 64 samples form the gradient in the backward sweep
+    # short rows and small layers run as two half-batches on two streams; layers of >= 4096 rows form the gradient in
+    # the backward sweep where a launch holds at most 64 samples (short rows) or the batch at most 256 (long rows)
     short_rows = nnz_total < 128 * N * L
     split = short_rows and Bt % 128 == 0 and N * Bt <= 2 ** 21
     fuse_opt = args.fuse_gradient if headline else 0
-    fused = (short_rows and (N >= 4096 or fuse_opt > 0) and fuse_opt >= 0
-             and ((split and Bt == 128) or (not split and 1 < Bt <= 64)))
+    fused = ((N >= 4096 or fuse_opt > 0) and fuse_opt >= 0
+             and ((short_rows and ((split and Bt == 128) or (not split and 1 < Bt <= 64)))
+                  or (not short_rows and Bt <= 256 and Bt % 4 == 0)))
     if split:
         v = 4 if Bt % 512 == 0 else 2 if Bt % 256 == 0 else 1
     else:
@@ -186,7 +187,7 @@ def run_config(cfg, args, steps, warmup, headline):
     bb -= (4 * first.n_in * Bt) if fused else layer_bytes(first.n_out, first.nnz, Bt, fused)[1]
     panels = short_rows and N * 256 >= (8 << 20) and (args.panel_cols >= 0 or not headline)   # the library's policy
     kernels = {"forward": "k_spmm_panel<8,0>" if panels else f"k_spmm<{v},0,{8 if short_rows else 16}>",
-               "backward": "k_bwd_grad<8>" if fused else f"k_spmm<{v},1,{8 if short_rows else 16}>",
+               "backward": ("k_bwd_grad<8>" if short_rows else "k_bwd_grad4<8>") if fused else f"k_spmm<{v},1,{8 if short_rows else 16}>",
                "update": "k_apply + k_gather_vals + k_apply_bias" if fused else "k_update<4>"}
     passes = {"forward": (fwd_ms, fb, L), "backward": (bwd_ms, bb, L if fused else L - 1), "update": (upd_ms, ub, 1)}
     dom = max(passes, key=lambda k: passes[k][0])

@@ -720,7 +720,6 @@ __device__ __forceinline__ void spmm_row_grad(RowMeta m, const SpmmArgs &a, unsi
     }
     if (a.store_out && live) a.out[(size_t)m.row * ld + s] = act_backprop(a.act, acc, xp, a.cap);
 }
-
 template <int U>
 __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad(const SpmmArgs a)
 {
@@ -735,6 +734,95 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad(const SpmmArgs a)
         if (r >= a.n_rows) continue;
         const RowMeta m = load_meta<0>(a.sched, a.idx, a.vals, nullptr, r, lane);
         spmm_row_grad<U>(m, a, tile + a.tile_base, lane, dt[wave], xt[wave]);
+    }
+}
+
+// The same sweep for long rows and a batch of up to 256 samples in one launch: four samples per lane, as in the long-row
+// product kernels, a gathered row of Delta_l being 1 KiB.  Eight entries are parked at a time ([entry][256 samples],
+// padded: 8.3 KB per wavefront, four wavefronts per SIMD); lane (e, q) sums entry e over the q-th eighth of the
+// samples (32 of them), three shuffles add the eighths.
+#define GRAD4_LD 260 // floats per parked entry: 256 samples + pad
+#define GRAD4_GE 8
+template <int U>
+__global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad4(const SpmmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float dt_all[WAVES_PER_BLOCK][GRAD4_GE * GRAD4_LD];
+    __shared__ __attribute__((aligned(16))) float xt_all[WAVES_PER_BLOCK][256];
+    const int lane = threadIdx.x & 63;
+    const unsigned wave = threadIdx.x >> 6;
+    float *__restrict__ dt = dt_all[wave];
+    float *__restrict__ xt = xt_all[wave];
+    const int B = a.B; // a multiple of 4, at most 256: one tile
+    const size_t ld = (size_t)B;
+    const unsigned ldb = 4u * (unsigned)B;
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
+    const int s_own = 4 * lane;
+    const bool live = s_own < B;
+    const int s = live ? s_own : 0;
+    const unsigned so = 4u * (unsigned)s;
+    const int e = lane & (GRAD4_GE - 1), q = lane / GRAD4_GE; // reducer of entry e over samples 32 q .. 32 q + 31
+    for (unsigned vb = blockIdx.x; vb < a.n_vblocks; vb += gridDim.x) {
+        const int r = __builtin_amdgcn_readfirstlane((int)(vb * WAVES_PER_BLOCK + wave));
+        if (r >= a.n_rows) continue;
+        const RowMeta m = load_meta<0>(a.sched, a.idx, a.vals, nullptr, r, lane);
+        float xp[4];
+        ldv<4>(a.aux + (size_t)m.row * ld + s, xp); // X_{l-1}(i, s ..): mask operand and gradient operand
+        wave_lds_sync();                            // the previous row's X values have been read
+        {
+            float4 xz = make_float4(0.0f, 0.0f, 0.0f, 0.0f); // samples outside the batch add nothing to the gradient
+            if (live) xz = make_float4(xp[0], xp[1], xp[2], xp[3]);
+            *reinterpret_cast<float4 *>(xt + 4 * lane) = xz;
+        }
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        int c_l = m.c_l, p_l;
+        float w_l = m.w_l;
+        for (int base = m.beg; base < m.end; base += 64) {
+            const int n = min(64, m.end - base);
+            if (base != m.beg) load_chunk<0>(a.idx, a.vals, nullptr, base, m.end, lane, c_l, w_l, p_l);
+            for (int g0 = 0; g0 < n; g0 += GRAD4_GE) {
+                const int ng = min(GRAD4_GE, n - g0);
+                for (int g = 0; g < ng; g += U) {
+                    float x[U][4];
+#pragma unroll
+                    for (int k = 0; k < U; ++k)
+                        if (g + k < ng) // wave-uniform
+                            gatherv<4>(rin, so, (unsigned)__builtin_amdgcn_readlane(c_l, g0 + g + k) * ldb, x[k]);
+#pragma unroll
+                    for (int k = 0; k < U; ++k)
+                        if (g + k < ng) {
+                            const double wk = (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_l), g0 + g + k));
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+                            *reinterpret_cast<float4 *>(dt + (g + k) * GRAD4_LD + 4 * lane) = make_float4(x[k][0], x[k][1], x[k][2], x[k][3]);
+                        }
+                }
+                wave_lds_sync(); // the lanes now read what other lanes of the wavefront have parked
+                double sum = 0.0;
+                if (e < ng) {
+                    const float4 *dp = reinterpret_cast<const float4 *>(dt + e * GRAD4_LD + 32 * q);
+                    const float4 *xq = reinterpret_cast<const float4 *>(xt + 32 * q);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const float4 d4 = dp[t], x4 = xq[t];
+                        sum = fma((double)d4.x, (double)x4.x, sum);
+                        sum = fma((double)d4.y, (double)x4.y, sum);
+                        sum = fma((double)d4.z, (double)x4.z, sum);
+                        sum = fma((double)d4.w, (double)x4.w, sum);
+                    }
+                }
+                sum += __shfl_xor(sum, 8);
+                sum += __shfl_xor(sum, 16);
+                sum += __shfl_xor(sum, 32);
+                if (q == 0 && e < ng) a.g_part[base + g0 + e] = (float)sum; // the entry's place in the transposed index
+                wave_lds_sync(); // the next group's rows are parked over the ones just read
+            }
+        }
+        if (a.store_out && live) {
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] = act_backprop(a.act, acc[v], xp[v], a.cap);
+            stv<4>(a.out + (size_t)m.row * ld + s, o);
+        }
     }
 }
 
@@ -1356,6 +1444,7 @@ struct sdnn_net {
     int n_cu = 0;                 // compute units of the device
     int occ_spmm[2][3][2][2] = {}; // resident workgroups per CU of k_spmm<V,MODE,U,tiles inner>, U = 8, 16
     int occ_grad = 0;             // the same for k_bwd_grad
+    int grad_v = 1;               // samples per lane of the fused sweep of the last backward pass (1: k_bwd_grad, 4: k_bwd_grad4)
     int occ_panel[2][4] = {};     // the same for k_spmm_panel<R,MODE>, R = 1, 2, 4, 8
     std::vector<int32_t> max_len[2]; // per layer: longest row of W (0) and of W^T (1)
     std::vector<char> clustered[2];  // per layer: reorder_rows found clusters in W (0), in W^T (1)
@@ -1465,7 +1554,8 @@ static int check_config(const sdnn_layer *layers, int32_t n_layers, const sdnn_c
 // The fused backward + gradient kernels pay from layers of 4096 rows on, whose launches are bound by gather
 // throughput; below that, where the latency of a launch binds, the separate update is faster (measured step
 // time against the separate kernels: 1024 rows +10 %, 4096 rows -5 %, 16384 rows -20 %, 65536 rows -30 %).
-// Nets with long rows never take the fused kernels (grad_fusable), so AUTO sets nothing up for them.
+// Nets with long rows take the fused sweep for batches of up to 256 samples (grad_fusable): AUTO sets it up for
+// them when max_batch allows it.
 static bool grad_buffers_wanted(const sdnn_layer *layers, int32_t n_layers, const sdnn_config *cfg)
 {
     if (!cfg->training || cfg->fuse_gradient == SDNN_FUSE_OFF) return false;
@@ -1475,7 +1565,8 @@ static bool grad_buffers_wanted(const sdnn_layer *layers, int32_t n_layers, cons
         rows += layers[l].n_out;
         nnz += layers[l].row_ptr ? layers[l].row_ptr[layers[l].n_out] : 0;
     }
-    return rows >= (int64_t)4096 * n_layers && nnz < 128 * rows;
+    // long rows: fused where the whole batch fits one launch of the four-samples-per-lane sweep
+    return rows >= (int64_t)4096 * n_layers && (nnz < 128 * rows || cfg->max_batch <= 256);
 }
 
 // The LDS-resident forward (k_fwd_lds) carries LDS_T samples through all layers with two activation
@@ -2376,6 +2467,15 @@ static int launch_bwd_grad(sdnn_net *net, const LayerDev &d, float *out, int B, 
     a.n_tiles = 1;
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     a.n_vblocks = a.n_rg;
+    if (net->grad_v == 4) {
+        // long, uneven rows: one workgroup per four rows, so that the hardware hands out the rows, longest first, as
+        // wavefronts retire
+        a.tile_base = 0;
+        void *args4[] = {(void *)&a};
+        HIP_TRY(net, hipLaunchKernel((const void *)k_bwd_grad4<8>, dim3(a.n_vblocks), dim3(BLOCK_THREADS), args4, 0, stream));
+        HIP_TRY(net, hipGetLastError());
+        return SDNN_OK;
+    }
     const void *fn = (const void *)k_bwd_grad<8>;
     if (net->occ_grad == 0) {
         HIP_TRY(net, hipOccupancyMaxActiveBlocksPerMultiprocessor(&net->occ_grad, fn, BLOCK_THREADS, 0));
@@ -2391,12 +2491,17 @@ static int launch_bwd_grad(sdnn_net *net, const LayerDev &d, float *out, int B, 
 
 // The fused kernels take launches of at most 64 samples with one sample per lane: the whole batch
 // (B <= 64) or its two halves on two streams (B = 128 on small layers); rows must be short.
-static int grad_fusable(const sdnn_net *net, int B, int sv)
+static int grad_fusable(const sdnn_net *net, int B, int sv, int *v)
 {
+    *v = 1;
     if (B == 1 || net->layers[0].G[0] == nullptr) return 0;
     int64_t nnz = 0, rows = 0;
     for (const LayerDev &d : net->layers) { nnz += d.nnz; rows += d.n_out; }
-    if (nnz >= 128 * rows) return 0;
+    if (nnz >= 128 * rows) { // long rows: the whole batch in one launch, four samples per lane (k_bwd_grad4)
+        if (B > 256 || B % 4 != 0) return 0;
+        *v = 4;
+        return 1;
+    }
     if (sv == 1 && B == 128) return 2;
     if (sv == 0 && B <= 64) return 1;
     return 0;
@@ -2419,7 +2524,7 @@ extern "C" int sdnn_backward(sdnn_net *net, const float *d_dLoss, void *stream_)
         HIP_TRY(net, hipGetLastError());
     }
     const int sv = split_v(net, B);
-    const int gp = grad_fusable(net, B, sv);
+    const int gp = grad_fusable(net, B, sv, &net->grad_v);
     net->grad_parts = gp;
     if (gp && net->vals_t_stale) { // the CSR values were replaced or stepped by the separate update since the last sweep
         int max_nnz = 0;

@@ -509,3 +509,36 @@ def test_fused_gradient_layout_at_the_sizes_of_its_spans_and_chunks():
             layers[k].values, layers[k].bias = gv, gb
         assert (deltas[5] != 0).any() and (deltas[6] != 0).any()
     net.close()
+
+
+@pytest.mark.parametrize("b", [256, 96, 36, 4, 130])
+def test_fused_gradient_on_long_rows_four_samples_per_lane(b):
+    """Rows of hundreds of entries (heavy-tailed degrees, and a layer with rows of 270 to 939 entries): the
+    backward sweep forms the gradient with four samples per lane for batches of up to 256 samples that are a multiple
+    of four; b = 130 takes the separate kernels on the same net.  Two steps, weights carried over."""
+    work = wl.make_config(5, n=1024, n_layers=3, b_infer=2 * b, b_train=b)
+    layers = work.layers + [wl.ragged_layer(8500, 700, 1024, 0.3, 3, 900, 5, 400)]
+    assert sum(l.nnz for l in layers) >= 128 * sum(l.n_out for l in layers)
+    x = wl.normal_inputs(8501, 1024, 2 * b)
+    tg = wl.uniform_targets(8502, 700, 2 * b)
+    net = sdnn.Net(layers, float("inf"), b, training=True, fuse_gradient=1)
+    for s in range(2):
+        x0 = np.ascontiguousarray(x[:, s * b:(s + 1) * b])
+        y = np.ascontiguousarray(tg[:, s * b:(s + 1) * b])
+        xl = torch.empty(700, b, device=P.DEV)
+        net.sdnn_forward(P.dev(x0), xl)
+        net.sdnn_backward(sdnn.sdnn_mse_dloss(xl, P.dev(y)))
+        got_d = [P.host(net.sdnn_get_delta(k, b)) for k in range(1, 5)]
+        got_g = [tuple(P.host(t) for t in net.sdnn_weight_grad(k)) for k in range(1, 5)]
+        net.sdnn_sgd_step(0.01)
+        xs, deltas, grads, new = P.O32.train_step(layers, x0, float("inf"), lambda v: P.mse_dloss(v, y), 0.01)
+        assert np.array_equal(P.host(xl), xs[-1]), f"step {s}: X_L"
+        for k in range(4):
+            assert np.array_equal(got_d[k], deltas[k + 1]), f"step {s}: delta {k + 1}"
+            P.assert_grad_close(got_g[k][0], grads[k][0], f"step {s} layer {k + 1} gradient")
+            P.assert_grad_close(got_g[k][1], grads[k][1], f"step {s} layer {k + 1} bias gradient")
+            gv, gb = (P.host(t) for t in net.sdnn_get_weights(k + 1))
+            P.assert_grad_close(gv, new[k][0], f"step {s} layer {k + 1} weights")
+            layers[k].values, layers[k].bias = gv, gb
+        assert all((g[0] != 0).any() for g in grads)
+    net.close()
