@@ -90,14 +90,17 @@ typedef struct {
     int32_t lds_forward; /* SDNN_LDS_AUTO / _ON / _OFF, see below                  */
 } sdnn_config;
 
-/* Where the batch allows it (at most 64 samples per launch, short rows), sdnn_backward can form
- * the gradient of the stored entries (Eq. 4) in the same sweep that back-propagates through W_l
- * (Eq. 7): both need the rows of Delta_l that an entry points at.  The net then keeps the values a
- * second time, in the order of the transposed index, which that sweep reads in a stream; the
+/* Where the batch allows it, sdnn_backward can form the gradient of the stored entries (Eq. 4) in
+ * the same sweep that back-propagates through W_l (Eq. 7): both need the rows of Delta_l that an
+ * entry points at.  Short rows (fewer than 128 entries on average): launches of at most 64 samples,
+ * i.e. B <= 64, or B = 128 as two halves; long rows: B <= 256 and a multiple of 4 (four samples per
+ * lane); other batch sizes take the separate kernels on the same net.  The net then keeps the values
+ * a second time, in the order of the transposed index, which that sweep reads in a stream; the
  * gradient is left in the same order, sdnn_sgd_step is a streaming pass over both and rebuilds the
  * CSR copy in a second pass that moves whole runs of entries.  Same results within the rounding of
  * the sum over samples; costs 24 more bytes of workspace per stored entry.  AUTO turns it on for
- * nets with short rows whose layers have 4096 rows or more on average, where it is faster. */
+ * nets whose layers have 4096 rows or more on average (long rows: if max_batch <= 256), where it is
+ * faster. */
 #define SDNN_FUSE_AUTO 0
 #define SDNN_FUSE_ON 1
 #define SDNN_FUSE_OFF (-1)
