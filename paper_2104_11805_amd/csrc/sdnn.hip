@@ -257,7 +257,10 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
     float w_l = m.w_l;
     for (int base = m.beg; base < m.end; base += 64) {
         const int n = min(64, m.end - base);
-        if (base != m.beg) load_chunk<MODE>(idx, vals, perm, base, m.end, lane, c_l, w_l, p_l);
+        // the entries of the next 64 are requested before this chunk's gathers, not after them
+        int c_n = 0, p_n = 0;
+        float w_n = 0.0f;
+        if (base + 64 < m.end) load_chunk<MODE>(idx, vals, perm, base + 64, m.end, lane, c_n, w_n, p_n);
         for (int g = 0; g < n; g += U) {
             float x[U][V];
             if (g + U <= n) {
@@ -289,6 +292,9 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
                     }
             }
         }
+        c_l = c_n;
+        w_l = w_n;
+        p_l = p_n;
     }
 
     float o[V];
@@ -778,7 +784,9 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad4(const SpmmArgs a)
         float w_l = m.w_l;
         for (int base = m.beg; base < m.end; base += 64) {
             const int n = min(64, m.end - base);
-            if (base != m.beg) load_chunk<0>(a.idx, a.vals, nullptr, base, m.end, lane, c_l, w_l, p_l);
+            int c_n = 0, p_n = 0; // the entries of the next 64 are requested before this chunk's gathers
+            float w_n = 0.0f;
+            if (base + 64 < m.end) load_chunk<0>(a.idx, a.vals, nullptr, base + 64, m.end, lane, c_n, w_n, p_n);
             for (int g0 = 0; g0 < n; g0 += GRAD4_GE) {
                 const int ng = min(GRAD4_GE, n - g0);
                 for (int g = 0; g < ng; g += U) {
@@ -816,6 +824,8 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad4(const SpmmArgs a)
                 if (q == 0 && e < ng) a.g_part[base + g0 + e] = (float)sum; // the entry's place in the transposed index
                 wave_lds_sync(); // the next group's rows are parked over the ones just read
             }
+            c_l = c_n;
+            w_l = w_n;
         }
         if (a.store_out && live) {
             float o[4];
