@@ -252,6 +252,53 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
 
+    // Long rows (U == 16), forward: a row's entries are the same for all lanes and never change inside a kernel, so they
+    // are read through the scalar cache, 16 columns and 16 weights at a time and a group ahead, straight into scalar
+    // registers: no lane broadcasts (2 of 11 vector instructions per entry at four samples per lane).
+    if constexpr (MODE == 0 && U == 16) {
+        typedef int i32x16 __attribute__((ext_vector_type(16)));
+        typedef float f32x16 __attribute__((ext_vector_type(16)));
+        const int __attribute__((address_space(4))) *sidx = (const int __attribute__((address_space(4))) *)idx;
+        const float __attribute__((address_space(4))) *svals = (const float __attribute__((address_space(4))) *)vals;
+        int g = m.beg;
+        i32x16 c, cn;
+        f32x16 w, wn;
+        if (g + 16 <= m.end) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) { c[k] = sidx[g + k]; w[k] = svals[g + k]; }
+        }
+        for (; g + 16 <= m.end; g += 16) {
+            if (g + 32 <= m.end) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) { cn[k] = sidx[g + 16 + k]; wn[k] = svals[g + 16 + k]; }
+            }
+            float x[16][V];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) gatherv<V>(rin, so, (unsigned)c[k] * ldb, x[k]);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const double wk = (double)w[k];
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+            }
+            c = cn;
+            w = wn;
+        }
+        if (g < m.end) { // the row's last entries, fewer than 16: same order, every entry guarded (wave-uniform)
+            const int n = m.end - g;
+            float x[16][V];
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (k < n) gatherv<V>(rin, so, (unsigned)sidx[g + k] * ldb, x[k]);
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (k < n) {
+                    const double wk = (double)svals[g + k];
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+                }
+        }
+    } else {
     // U gathers are in flight per lane before the first of them is consumed
     int c_l = m.c_l, p_l = m.p_l;
     float w_l = m.w_l;
@@ -295,6 +342,7 @@ __device__ __forceinline__ void spmm_row(RowMeta m, const int32_t *idx, const fl
         c_l = c_n;
         w_l = w_n;
         p_l = p_n;
+    }
     }
 
     float o[V];
@@ -770,7 +818,16 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad4(const SpmmArgs a)
     for (unsigned vb = blockIdx.x; vb < a.n_vblocks; vb += gridDim.x) {
         const int r = __builtin_amdgcn_readfirstlane((int)(vb * WAVES_PER_BLOCK + wave));
         if (r >= a.n_rows) continue;
-        const RowMeta m = load_meta<0>(a.sched, a.idx, a.vals, nullptr, r, lane);
+        // the row's task record and its entries are the same for all lanes and do not change inside the kernel: they
+        // are read through the scalar cache into scalar registers, eight columns and eight weights a group ahead
+        typedef int i32x4s __attribute__((ext_vector_type(4)));
+        typedef int i32x8 __attribute__((ext_vector_type(8)));
+        typedef float f32x8 __attribute__((ext_vector_type(8)));
+        const i32x4s task = ((const i32x4s __attribute__((address_space(4))) *)a.sched)[r];
+        RowMeta m;
+        m.row = task.x; m.beg = task.y; m.end = task.z;
+        const int __attribute__((address_space(4))) *sidx = (const int __attribute__((address_space(4))) *)a.idx;
+        const float __attribute__((address_space(4))) *svals = (const float __attribute__((address_space(4))) *)a.vals;
         float xp[4];
         ldv<4>(a.aux + (size_t)m.row * ld + s, xp); // X_{l-1}(i, s ..): mask operand and gradient operand
         wave_lds_sync();                            // the previous row's X values have been read
@@ -780,52 +837,72 @@ __global__ void __launch_bounds__(BLOCK_THREADS) k_bwd_grad4(const SpmmArgs a)
             *reinterpret_cast<float4 *>(xt + 4 * lane) = xz;
         }
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        int c_l = m.c_l, p_l;
-        float w_l = m.w_l;
-        for (int base = m.beg; base < m.end; base += 64) {
-            const int n = min(64, m.end - base);
-            int c_n = 0, p_n = 0; // the entries of the next 64 are requested before this chunk's gathers
-            float w_n = 0.0f;
-            if (base + 64 < m.end) load_chunk<0>(a.idx, a.vals, nullptr, base + 64, m.end, lane, c_n, w_n, p_n);
-            for (int g0 = 0; g0 < n; g0 += GRAD4_GE) {
-                const int ng = min(GRAD4_GE, n - g0);
-                for (int g = 0; g < ng; g += U) {
-                    float x[U][4];
+        static_assert(U == GRAD4_GE, "a parked group is one batch of gathers");
+        // reduces the ng parked entries over the samples and stores their gradients at entries g .. g + ng - 1
+        auto reduce_parked = [&](int g, int ng) {
+            wave_lds_sync(); // the lanes now read what other lanes of the wavefront have parked
+            double sum = 0.0;
+            if (e < ng) {
+                const float4 *dp = reinterpret_cast<const float4 *>(dt + e * GRAD4_LD + 32 * q);
+                const float4 *xq = reinterpret_cast<const float4 *>(xt + 32 * q);
 #pragma unroll
-                    for (int k = 0; k < U; ++k)
-                        if (g + k < ng) // wave-uniform
-                            gatherv<4>(rin, so, (unsigned)__builtin_amdgcn_readlane(c_l, g0 + g + k) * ldb, x[k]);
-#pragma unroll
-                    for (int k = 0; k < U; ++k)
-                        if (g + k < ng) {
-                            const double wk = (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_l), g0 + g + k));
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
-                            *reinterpret_cast<float4 *>(dt + (g + k) * GRAD4_LD + 4 * lane) = make_float4(x[k][0], x[k][1], x[k][2], x[k][3]);
-                        }
+                for (int t = 0; t < 8; ++t) {
+                    const float4 d4 = dp[t], x4 = xq[t];
+                    sum = fma((double)d4.x, (double)x4.x, sum);
+                    sum = fma((double)d4.y, (double)x4.y, sum);
+                    sum = fma((double)d4.z, (double)x4.z, sum);
+                    sum = fma((double)d4.w, (double)x4.w, sum);
                 }
-                wave_lds_sync(); // the lanes now read what other lanes of the wavefront have parked
-                double sum = 0.0;
-                if (e < ng) {
-                    const float4 *dp = reinterpret_cast<const float4 *>(dt + e * GRAD4_LD + 32 * q);
-                    const float4 *xq = reinterpret_cast<const float4 *>(xt + 32 * q);
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const float4 d4 = dp[t], x4 = xq[t];
-                        sum = fma((double)d4.x, (double)x4.x, sum);
-                        sum = fma((double)d4.y, (double)x4.y, sum);
-                        sum = fma((double)d4.z, (double)x4.z, sum);
-                        sum = fma((double)d4.w, (double)x4.w, sum);
-                    }
-                }
-                sum += __shfl_xor(sum, 8);
-                sum += __shfl_xor(sum, 16);
-                sum += __shfl_xor(sum, 32);
-                if (q == 0 && e < ng) a.g_part[base + g0 + e] = (float)sum; // the entry's place in the transposed index
-                wave_lds_sync(); // the next group's rows are parked over the ones just read
             }
-            c_l = c_n;
-            w_l = w_n;
+            sum += __shfl_xor(sum, 8);
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            if (q == 0 && e < ng) a.g_part[g + e] = (float)sum; // the entry's place in the transposed index
+            wave_lds_sync(); // the next group's rows are parked over the ones just read
+        };
+        int g = m.beg;
+        i32x8 c, cn;
+        f32x8 w, wn;
+        if (g + 8 <= m.end) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { c[k] = sidx[g + k]; w[k] = svals[g + k]; }
+        }
+        for (; g + 8 <= m.end; g += 8) {
+            if (g + 16 <= m.end) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) { cn[k] = sidx[g + 8 + k]; wn[k] = svals[g + 8 + k]; }
+            }
+            float x[8][4];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) gatherv<4>(rin, so, (unsigned)c[k] * ldb, x[k]);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                float wf = w[k];
+                asm volatile("" : "+s"(wf)); // converted when it is used, not while the gathers are in flight
+                const double wk = (double)wf;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+                *reinterpret_cast<float4 *>(dt + k * GRAD4_LD + 4 * lane) = make_float4(x[k][0], x[k][1], x[k][2], x[k][3]);
+            }
+            reduce_parked(g, 8);
+            c = cn;
+            w = wn;
+        }
+        if (g < m.end) { // the row's last entries, fewer than eight: same order, every entry guarded (wave-uniform)
+            const int n = m.end - g;
+            float x[8][4];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k < n) gatherv<4>(rin, so, (unsigned)sidx[g + k] * ldb, x[k]);
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k < n) {
+                    const double wk = (double)svals[g + k];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[v] = fma(wk, (double)x[k][v], acc[v]);
+                    *reinterpret_cast<float4 *>(dt + k * GRAD4_LD + 4 * lane) = make_float4(x[k][0], x[k][1], x[k][2], x[k][3]);
+                }
+            reduce_parked(g, n);
         }
         if (a.store_out && live) {
             float o[4];
