@@ -542,3 +542,26 @@ def test_fused_gradient_on_long_rows_four_samples_per_lane(b):
             layers[k].values, layers[k].bias = gv, gb
         assert all((g[0] != 0).any() for g in grads)
     net.close()
+
+
+def test_fused_gradient_long_row_kernels_on_empty_and_short_rows():
+    """A net that is dense enough overall to take the long-row kernels (scalar entry loads, four samples per lane)
+    also has a layer with empty rows, empty columns and rows of one to seven entries: every group size of the
+    scalar loads and of the parked rows, and rows with nothing to do."""
+    dense = wl.random_layer(8601, 600, 600, 0.6, scale=0.05)
+    sparse = wl.ragged_layer(8602, 300, 600, 0.003, 2, 333, 2, 150)
+    tail = wl.random_layer(8603, 64, 300, 0.5, scale=0.2)
+    layers = [dense, sparse, tail]
+    lens = np.diff(sparse.row_ptr)
+    cols = np.bincount(sparse.col_idx, minlength=600)
+    assert (lens == 0).any() and (cols == 0).any() and ((lens > 0) & (lens < 8)).any() and lens.max() > 300
+    assert sum(l.nnz for l in layers) >= 128 * sum(l.n_out for l in layers)
+    b = 100
+    x = wl.normal_inputs(8690, 600, b)
+    tg = wl.uniform_targets(8691, 64, b)
+    work = wl.Workload("long-row-edges", layers, float("inf"), x, b, "mse", 0.02, targets=tg)
+    o = P.oracle_train_step(work, x)
+    for fuse in (1, -1):
+        g = P.gpu_train_step(work, x, fuse_gradient=fuse)
+        st = P.compare_step(g, o, f"long-row edges fuse={fuse}")
+        assert st["bitexact_x"] == 4 and st["bitexact_d"] == 3 and st["live_g"] == 3
