@@ -413,7 +413,7 @@ def paper_setup_bench(args, np, torch, sdnn, wl):
     dev = "cuda:0"
     L = args.layers or 120
     work = wl.paper_training_setup(args.n, n_layers=L, n_inputs=64)
-    net = sdnn.Net(work.layers, work.act_cap, 1, training=True, activation="sigmoid")
+    net = sdnn.Net(work.layers, work.act_cap, 1, training=True, activation="sigmoid", fuse_gradient=args.fuse_gradient)
     xs = [torch.from_numpy(np.ascontiguousarray(work.x_infer[:, s:s + 1])).to(dev) for s in range(64)]
     ys = [torch.from_numpy(np.ascontiguousarray(work.targets[:, s:s + 1])).to(dev) for s in range(64)]
     xl = torch.empty(args.n, 1, device=dev)

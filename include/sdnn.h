@@ -94,7 +94,9 @@ typedef struct {
  * the same sweep that back-propagates through W_l (Eq. 7): both need the rows of Delta_l that an
  * entry points at.  Short rows (fewer than 128 entries on average): launches of at most 64 samples,
  * i.e. B <= 64, or B = 128 as two halves; long rows: B <= 256 and a multiple of 4 (four samples per
- * lane); other batch sizes take the separate kernels on the same net.  The net then keeps the values
+ * lane); one sample per step (B = 1) on a net created with max_batch == 1 whose layers all have 8192
+ * inputs or more and short rows (4 more bytes per entry then); other batch sizes take the separate
+ * kernels on the same net.  The net then keeps the values
  * a second time, in the order of the transposed index, which that sweep reads in a stream; the
  * gradient is left in the same order, sdnn_sgd_step is a streaming pass over both and rebuilds the
  * CSR copy in a second pass that moves whole runs of entries.  Same results within the rounding of

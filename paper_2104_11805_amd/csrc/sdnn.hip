@@ -1061,6 +1061,73 @@ __global__ void __launch_bounds__(64) k_spmv_stage(const SpmmArgs a, int R)
     }
 }
 
+// The same kernel as the backward sweep of a one-sample step that also forms the gradient (B = 1 has no sum over
+// samples: g(j, i) = Delta_l(j) X_{l-1}(i), one product per entry).  The rows are those of W_l^T, the values are read
+// from their copy in that order, and the lane that holds entry (j, i) for the product also has Delta_l(j); it fetches
+// X_{l-1}(i) through t_col and stores the gradient at the entry's place in the transposed index, in a stream.
+template <int J>
+__global__ void __launch_bounds__(64) k_spmv_stage_grad(const SpmmArgs a, int R, const int32_t *__restrict__ t_col)
+{
+    __shared__ double prod[SPMV_STAGE + SPMV_STAGE / 32];
+    const int lane = threadIdx.x;
+    const int r0 = blockIdx.x * R;
+    const int nr = min(R, a.n_rows - r0); // >= 1 by the grid size
+    const int row = r0 + lane;
+    int p = 0, end = 0;
+    if (lane < nr) { p = a.row_ptr[row]; end = a.row_ptr[row + 1]; }
+    const int e0 = a.row_ptr[r0], e1 = a.row_ptr[r0 + nr];
+    double acc = 0.0;
+    for (int sb = e0; sb < e1; sb += SPMV_STAGE) {
+        const int se = min(sb + SPMV_STAGE, e1);
+        for (int j0 = 0; j0 * 64 < se - sb; j0 += J) {
+            int c[J], ti[J];
+            float w[J], x[J], xi[J];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                const int e = sb + (j0 + j) * 64 + lane;
+                c[j] = -1;
+                if (e < se) {
+                    c[j] = a.idx[e];
+                    w[j] = a.vals[e];
+                    ti[j] = t_col[e];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < J; ++j)
+                if (c[j] >= 0) {
+                    x[j] = a.in[c[j]];
+                    xi[j] = a.aux[ti[j]];
+                }
+#pragma unroll
+            for (int j = 0; j < J; ++j)
+                if (c[j] >= 0) {
+                    const int q = (j0 + j) * 64 + lane;
+                    prod[q + (q >> 5)] = (double)w[j] * (double)x[j];
+                    a.g_part[sb + q] = (float)((double)x[j] * (double)xi[j]);
+                }
+        }
+        if (!a.store_out) continue; // first layer: only the gradient (uniform for the workgroup)
+        __syncthreads();
+        const int pe = min(end, se); // my row's entries inside this segment are [p, pe)
+        if (p < pe) {
+            for (; p < pe; p += 4) { // four parked products requested together, added one after the other
+                double v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int q = min(p + k, pe - 1) - sb;
+                    v[k] = prod[q + (q >> 5)];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (p + k < pe) acc += v[k];
+            }
+            p = pe;
+        }
+        __syncthreads();
+    }
+    if (a.store_out && lane < nr) a.out[row] = act_backprop(a.act, acc, a.aux[row], a.cap);
+}
+
 // Update for B = 1: no sum over samples, so the lanes take the entries of the rows:
 // vals[p] -= lr * delta(row) * x(col[p]).  A wavefront holds 64 >> lpr_log2 rows of 1 << lpr_log2
 // lanes each (chosen from the mean row length, so that short rows do not idle half the lanes);
@@ -1531,7 +1598,8 @@ struct sdnn_net {
     int n_cu = 0;                 // compute units of the device
     int occ_spmm[2][3][2][2] = {}; // resident workgroups per CU of k_spmm<V,MODE,U,tiles inner>, U = 8, 16
     int occ_grad = 0;             // the same for k_bwd_grad
-    int grad_v = 1;               // samples per lane of the fused sweep of the last backward pass (1: k_bwd_grad, 4: k_bwd_grad4)
+    int grad_v = 1;               // samples per lane of the fused sweep of the last backward pass (1: k_bwd_grad, 4: k_bwd_grad4,
+                                  // 0: one sample per step, k_spmv_stage_grad)
     int occ_panel[2][4] = {};     // the same for k_spmm_panel<R,MODE>, R = 1, 2, 4, 8
     std::vector<int32_t> max_len[2]; // per layer: longest row of W (0) and of W^T (1)
     std::vector<char> clustered[2];  // per layer: reorder_rows found clusters in W (0), in W^T (1)
@@ -1603,7 +1671,7 @@ static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 // Workspace plan: offsets of every array, in one pass (also used to size it).
 struct Plan {
     struct PerLayer {
-        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2], vals_t, mid_slot, mid_dst, mid_loc, mid;
+        size_t row_ptr, col_idx, vals, bias, t_row_ptr, t_row_idx, t_perm, sched, t_sched, X, D, G[2], vals_t, mid_slot, mid_dst, mid_loc, mid, t_col;
         size_t lm, lm_off, lm_row, lm_bias, lm_entries, lm_blocks;
     };
     std::vector<PerLayer> pl;
@@ -1708,7 +1776,7 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
         const sdnn_layer &y = layers[l];
         nnz[l] = (size_t)y.row_ptr[y.n_out];
         Plan::PerLayer &q = pl.pl[l];
-        q.X = q.D = q.G[0] = q.G[1] = q.vals_t = q.mid_slot = q.mid_dst = q.mid_loc = q.mid = 0;
+        q.X = q.D = q.G[0] = q.G[1] = q.vals_t = q.mid_slot = q.mid_dst = q.mid_loc = q.mid = q.t_col = 0;
         q.lm = q.lm_off = q.lm_row = q.lm_bias = q.lm_entries = q.lm_blocks = 0;
         if (lm) {
             std::vector<int32_t> lens;
@@ -1751,6 +1819,7 @@ static void make_plan(const sdnn_layer *layers, int32_t n_layers, const sdnn_con
             PLAN_KIND(mid_dst, 4 * nnz[l])
             PLAN_KIND(mid_loc, 2 * nnz[l])
             PLAN_KIND(mid, 4 * nnz[l])
+            if (cfg->max_batch == 1) PLAN_KIND(t_col, 4 * nnz[l])
         }
     } else {
         pl.ping = take(4 * max_n * mb);
@@ -1836,6 +1905,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
         std::vector<float> vals_t;
         std::vector<int32_t> mid_dst;
         std::vector<uint16_t> mid_slot, mid_loc;
+        std::vector<int32_t> t_col;
         std::vector<int2> lm;
         std::vector<int32_t> lm_off, lm_row;
         std::vector<float> lm_bias;
@@ -1886,6 +1956,11 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 h.sched[r] = make_int4(h.order[r], y.row_ptr[h.order[r]], y.row_ptr[h.order[r] + 1], 0);
             for (int32_t r = 0; r < y.n_in; ++r)
                 h.t_sched[r] = make_int4(h.t_order[r], h.t_row_ptr[h.t_order[r]], h.t_row_ptr[h.t_order[r] + 1], 0);
+            if (gw_ && cfg->max_batch == 1) { // one sample per step: the fused sweep looks up each entry's row of W^T
+                h.t_col.resize(nnz);
+                for (int32_t i = 0; i < y.n_in; ++i)
+                    for (int32_t q = h.t_row_ptr[i]; q < h.t_row_ptr[i + 1]; ++q) h.t_col[(size_t)q] = i;
+            }
             if (gw_) { // the values in the order of the transposed index, for the fused backward sweep
                 h.vals_t.resize(nnz);
                 h.mid_slot.resize(nnz);
@@ -2011,6 +2086,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 d.mid_dst = gw ? (const int32_t *)(base + q.mid_dst) : nullptr;
                 d.mid_loc = gw ? (const uint16_t *)(base + q.mid_loc) : nullptr;
                 d.mid = gw ? (float *)(base + q.mid) : nullptr;
+                d.t_col = gw && cfg->max_batch == 1 ? (const int32_t *)(base + q.t_col) : nullptr;
                 d.lm = want_lm ? (int2 *)(base + q.lm) : nullptr;
                 d.lm_off = want_lm ? (const int32_t *)(base + q.lm_off) : nullptr;
                 d.lm_row = want_lm ? (const int32_t *)(base + q.lm_row) : nullptr;
@@ -2038,6 +2114,7 @@ extern "C" int sdnn_create(const sdnn_layer *layers, int32_t n_layers, const sdn
                 if (gw) UP(d.mid_slot, h.mid_slot.data(), 2 * nnz);
                 if (gw) UP(d.mid_dst, h.mid_dst.data(), 4 * nnz);
                 if (gw) UP(d.mid_loc, h.mid_loc.data(), 2 * nnz);
+                if (d.t_col) UP(d.t_col, h.t_col.data(), 4 * nnz);
                 if (want_lm) {
                     if (h.lm.size() != q.lm_entries)
                         return fail_free(fail(nullptr, SDNN_EINVAL, "layer %d: lane-major copy does not match its plan", l + 1));
@@ -2554,6 +2631,14 @@ static int launch_bwd_grad(sdnn_net *net, const LayerDev &d, float *out, int B, 
     a.n_tiles = 1;
     a.n_rg = (uint32_t)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     a.n_vblocks = a.n_rg;
+    if (net->grad_v == 0) { // B = 1
+        const int R = a.n_rows >= 32768 ? 16 : 8;
+        a.row_ptr = d.t_row_ptr;
+        const int32_t *t_col = d.t_col;
+        hipLaunchKernelGGL((k_spmv_stage_grad<8>), dim3((unsigned)((a.n_rows + R - 1) / R)), dim3(64), 0, stream, a, R, t_col);
+        HIP_TRY(net, hipGetLastError());
+        return SDNN_OK;
+    }
     if (net->grad_v == 4) {
         // long, uneven rows: one workgroup per four rows, so that the hardware hands out the rows, longest first, as
         // wavefronts retire
@@ -2581,7 +2666,16 @@ static int launch_bwd_grad(sdnn_net *net, const LayerDev &d, float *out, int B, 
 static int grad_fusable(const sdnn_net *net, int B, int sv, int *v)
 {
     *v = 1;
-    if (B == 1 || net->layers[0].G[0] == nullptr) return 0;
+    if (net->layers[0].G[0] == nullptr) return 0;
+    if (B == 1) { // one sample per step: wide layers with short rows only (among those that k_spmv_stage takes)
+        // measured step of the 120-layer sigmoid nets, fused vs separate: 65536 rows 6.39 vs 7.80 ms, 16384 rows 2.27
+        // vs 2.59, 4096 rows 1.57 vs 1.51 (launch-bound: one more launch per step than it saves)
+        if (net->layers[0].t_col == nullptr) return 0;
+        for (const LayerDev &d : net->layers)
+            if (d.n_in < 8192 || (int64_t)d.nnz >= 128 * (int64_t)d.n_in) return 0;
+        *v = 0;
+        return 1;
+    }
     int64_t nnz = 0, rows = 0;
     for (const LayerDev &d : net->layers) { nnz += d.nnz; rows += d.n_out; }
     if (nnz >= 128 * rows) { // long rows: the whole batch in one launch, four samples per lane (k_bwd_grad4)

@@ -27,6 +27,8 @@ struct LayerDev {
     float *D;                 // Delta_l  [n_out][B]  (training mode)
     float *G[2];              // [nnz] each: gradient of the stored entries over one half of the batch, in the order of
                               // the transposed index (fused backward sweep; training mode)
+    const int32_t *t_col;     // [nnz]: the row of W^T (column of W) of each entry of the transposed index; only on nets
+                              // created for one sample per step (max_batch == 1) with the fused sweep, NULL otherwise
     float *vals_t;            // [nnz]: the values in the order of the transposed index (vals_t[q] == vals[t_perm[q]]),
                               // read by the fused backward sweep; NULL where that sweep is not set up
     // The way back from the transposed order to the CSR order, in two passes that both move whole runs (NULL with

@@ -253,6 +253,12 @@ def test_one_vector_wide_layers_take_the_staged_kernels(activation):
     assert st["live_g"] == 3 and st["live_d"] == 3
     if activation == "relu":
         assert st["bitexact_d"] == 3
+    # the same step with the gradient formed in the backward sweep (one product per entry at B = 1)
+    gf = P.gpu_train_step(work, work.x_infer, lr=0.05, fuse_gradient=1)
+    stf = P.compare_step(gf, o, f"staged b=1 {activation}, fused", exact_fwd=(activation == "relu"))
+    assert stf["live_g"] == 3 and stf["live_d"] == 3
+    for k in range(1, 4):
+        assert np.array_equal(gf["deltas"][k], g["deltas"][k])
 
 
 def test_one_vector_rows_longer_than_a_stage():
@@ -269,6 +275,9 @@ def test_one_vector_rows_longer_than_a_stage():
     o = P.oracle_train_step(work, work.x_infer, lr=0.05)
     st = P.compare_step(g, o, "ragged b=1")
     assert st["bitexact_d"] == 2 and st["live_g"] == 2
+    gf = P.gpu_train_step(work, work.x_infer, lr=0.05, fuse_gradient=1)
+    stf = P.compare_step(gf, o, "ragged b=1, fused")
+    assert stf["bitexact_d"] == 2 and stf["live_g"] == 2
 
 
 def test_paper_training_setup_wide_net_two_steps():
